@@ -1,0 +1,156 @@
+/*
+ * ozdgemm.h -- C ABI of the MI355X (gfx950) emulated-DGEMM library.
+ *
+ * C = alpha * op(A) * op(B) + beta * C in FP64, computed with Ozaki scheme I on the INT8
+ * matrix units: FP64 operands are aligned per row of op(A) / per column of op(B), cut into
+ * 8-bit two's-complement digits ("slices") with the unsigned-slice encoding, the kept slice
+ * pairs are multiplied with exact int32 accumulation, and the integer products are recombined
+ * in FP64.  A device-resident guard (Inf/NaN scan, Exponent Span Capacity estimate, verdict)
+ * chooses the slice count or routes the call to a native FP64 GEMM, with no host-device
+ * synchronisation (paper: sections "Unsigned Slice Encoding", "ESC: Exponent Span Capacity
+ * Estimation", "ADP: Automatic Dynamic Precision", flowchart of the GEMM decision process).
+ *
+ * Conventions
+ *   - BLAS dgemm semantics, column-major.  op(X) = X for trans 'N'/'n', X^T for 'T'/'t'.
+ *     op(A) is m x k, op(B) is k x n, C is m x n.  lda >= max(1, rows of stored A), etc.
+ *   - A, B, C, workspace and result are DEVICE pointers owned by the caller.  A and B are only
+ *     read.  C is overwritten; it is not read when beta == 0.  The library never allocates or
+ *     frees device memory and never synchronises: a call only enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*) and returns.
+ *   - m == 0 or n == 0: nothing is done.  k == 0 or alpha == 0: C = beta * C.
+ *   - Return values report host-side argument errors only.  Numerical conditions (Inf/NaN in
+ *     the inputs, exponent span too wide, emulation predicted slower) are never errors: they
+ *     select the native FP64 path and are recorded in *result.
+ *   - Negative zeros in A and B are treated as zero.
+ */
+#ifndef OZDGEMM_H
+#define OZDGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct oz_handle* oz_handle_t;
+
+typedef enum {
+    OZ_OK = 0,
+    OZ_ERR_ARG = 1,        /* bad trans, negative size, leading dimension too small, bad option */
+    OZ_ERR_WORKSPACE = 2,  /* workspace NULL, misaligned (256 B) or smaller than required */
+    OZ_ERR_DEVICE = 3,     /* device is not gfx950 or cannot be selected */
+    OZ_ERR_HIP = 4         /* a HIP runtime call (launch, event) failed */
+} oz_status_t;
+
+/* How the slice count is chosen (section "Performance Evaluation": "no ADP", "ADP forced to
+ * 55 bits", "ADP in dynamic mode"; section "Numerical Accuracy": with/without fallback). */
+typedef enum {
+    OZ_DYNAMIC = 0,         /* scan + ESC; S = ceil((target_bits + ESC + 2) / 8); native FP64 on
+                               Inf/NaN, when target_bits + ESC > max_bits, or when the heuristic
+                               predicts emulation to be slower */
+    OZ_FORCED_GUARDED = 1,  /* scan + ESC run (their cost is paid), S forced from max_bits; only
+                               Inf/NaN selects the native path */
+    OZ_FIXED_GUARDED = 2,   /* S from max_bits; native path on Inf/NaN or target_bits + ESC > max_bits */
+    OZ_FIXED_UNGUARDED = 3, /* S from max_bits; no Inf/NaN test, no ESC, never falls back */
+    OZ_NATIVE = 4           /* always the FP64-MFMA GEMM */
+} oz_mode_t;
+
+typedef struct {
+    int32_t mode;         /* oz_mode_t */
+    int32_t target_bits;  /* mantissa bits to preserve for the dominant products (default 53) */
+    int32_t max_bits;     /* fixed modes: bits that set S = ceil((max_bits+1)/8) (55 -> 7 slices);
+                             guarded/dynamic modes: cap on target_bits + ESC.  1..200 */
+    int32_t slices;       /* > 0 overrides the slice count of the fixed/forced modes (1..26) */
+    int32_t esc_block;    /* block length b of the coarsened ESC; 0 = 64.  Multiple of 16, <= 1024 */
+    int32_t heuristic;    /* OZ_DYNAMIC only: 1 = apply the run-time cost model, 0 = do not */
+} oz_opts_t;
+
+/* Decision record, written to DEVICE memory by the verdict kernel. */
+typedef struct {
+    int32_t fallback;       /* 0 = emulated, 1 = native FP64 */
+    int32_t reason;         /* 0 none, 1 Inf/NaN in A or B, 2 bits > max_bits, 3 heuristic, 4 OZ_NATIVE */
+    int32_t slices_used;    /* S of the emulated path, 0 when fallback */
+    int32_t esc;            /* coarsened ESC (clamped to 4096), -1 when not computed */
+    int32_t required_bits;  /* target_bits + ESC, 0 when not computed */
+    int32_t infnan;         /* 1 when the scan saw an all-ones exponent field */
+} oz_result_t;
+
+/* Cost model of the run-time heuristic (section "Heuristic run time Selection"); integer
+ * arithmetic so that host, device and any checker agree bit for bit:
+ *   t_emu = fixed_ns + (2mnk / int8_ops_per_ns) * S(S+1)/2
+ *           + ((8+S)(mk+kn) + (8S+16)mn) / bytes_per_ns,      t_f64 = 2mnk / fp64_flops_per_ns,
+ * emulation is "slower" when t_emu > t_f64. */
+typedef struct {
+    int64_t int8_ops_per_ns;
+    int64_t fp64_flops_per_ns;
+    int64_t bytes_per_ns;
+    int64_t fixed_ns;
+} oz_heuristic_t;
+
+/* Creates a handle bound to HIP device `device` (must be gfx950).  Host memory only. */
+oz_status_t oz_create(oz_handle_t* handle, int device);
+oz_status_t oz_destroy(oz_handle_t handle);
+
+/* Fills *opts with the defaults: OZ_DYNAMIC, target 53, max 200, slices 0, esc_block 0, heuristic 1. */
+void oz_default_opts(oz_opts_t* opts);
+
+/* Replaces the heuristic's constants (defaults are calibrated for MI355X). */
+oz_status_t oz_set_heuristic(oz_handle_t handle, const oz_heuristic_t* model);
+
+/* Bytes of device workspace oz_dgemm needs for this problem and these options (sized for the
+ * largest slice count the options allow).  Returns 0 on invalid arguments. */
+size_t oz_dgemm_workspace_bytes(oz_handle_t handle, char transa, char transb,
+                                int64_t m, int64_t n, int64_t k, const oz_opts_t* opts);
+
+/* The call.  workspace: device, 256-byte aligned, >= oz_dgemm_workspace_bytes(...); its
+ * contents are scratch.  result: device, may be NULL.  Calls sharing a workspace must be
+ * ordered on one stream. */
+oz_status_t oz_dgemm(oz_handle_t handle, void* stream, char transa, char transb,
+                     int64_t m, int64_t n, int64_t k, double alpha,
+                     const double* A, int64_t lda, const double* B, int64_t ldb,
+                     double beta, double* C, int64_t ldc,
+                     const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
+                     oz_result_t* result);
+
+/* Layout of the intermediate buffers inside the workspace after an oz_dgemm call, for
+ * inspection by tests (all offsets in bytes from `workspace`):
+ *   eA   int32[mp]              row exponents of op(A); -12288 marks an all-zero row
+ *   eB   int32[np]              column exponents of op(B)
+ *   As   int8 [S_cap][kp/16][mp][16]   slice s of op(A): element (i,l) at
+ *                               ((s*(kp/16) + l/16)*mp + i)*16 + l%16; padding is zero
+ *   Bs   int8 [S_cap][kp/16][np][16]   slice t of op(B): element (l,j) likewise with j for i
+ *   P    int32[nkb][S_cap][np][mp]     anti-diagonal sums sum_{s+t=d} As_s Bs_t^T of k-block kb:
+ *                               element (i,j) at ((kb*S_cap + d)*np + j)*mp + i
+ * mp, np = m, n rounded up to 256; kp = k rounded up to 128; kblk = k-block length for S_cap. */
+typedef struct {
+    int64_t mp, np, kp, s_cap, nkb, kblk;
+    size_t off_eA, off_eB, off_As, off_Bs, off_P, off_record;
+    size_t total_bytes;
+} oz_layout_t;
+
+oz_status_t oz_dgemm_layout(oz_handle_t handle, char transa, char transb,
+                            int64_t m, int64_t n, int64_t k, const oz_opts_t* opts,
+                            oz_layout_t* layout);
+
+/* Stage timing with HIP events on the call's own stream.  oz_profile_enable(h, n) makes the
+ * next n oz_dgemm calls record an event after every stage; oz_profile_read(h, call, ms)
+ * (after the stream has been synchronised by the caller) writes OZ_NUM_STAGES durations in
+ * milliseconds.  Stages: 0 scan (Inf/NaN + exponent min/max), 1 ESC, 2 verdict,
+ * 3 slicing, 4 slice-pair INT8 GEMMs, 5 FP64 recomposition, 6 native FP64 GEMM. */
+#define OZ_NUM_STAGES 7
+oz_status_t oz_profile_enable(oz_handle_t handle, int32_t max_calls);
+oz_status_t oz_profile_read(oz_handle_t handle, int32_t call, float* stage_ms);
+
+/* Stand-alone native FP64-MFMA GEMM (the fallback kernel on its own), same conventions. */
+oz_status_t oz_native_dgemm(oz_handle_t handle, void* stream, char transa, char transb,
+                            int64_t m, int64_t n, int64_t k, double alpha,
+                            const double* A, int64_t lda, const double* B, int64_t ldb,
+                            double beta, double* C, int64_t ldc);
+
+const char* oz_status_string(oz_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OZDGEMM_H */

@@ -334,8 +334,31 @@ def slice_rows_int64(A: np.ndarray, eA: np.ndarray, S: int) -> np.ndarray:
     return out
 
 
+def fixed_point_shift(a: float, e_row: int, S: int) -> int:
+    """The same X as fixed_point, by integer shifts instead of rational arithmetic (faster):
+    a = mant * 2^(p-53) with the integer mant = frexp-significand * 2^53, so X is mant shifted
+    by p - 53 + q; Python's >> on a negative integer rounds toward -infinity."""
+    if a == 0.0 or e_row <= NEG_INF_BELOW:
+        return 0
+    f, p = math.frexp(a)
+    mant = int(f * 9007199254740992.0)          # exact: f has at most 53 significant bits
+    sh = p - 53 + (8 * S - 2 - H - e_row)
+    return mant << sh if sh >= 0 else mant >> (-sh)
+
+
+def slice_rows_bigint(A: np.ndarray, eA: np.ndarray, S: int) -> np.ndarray:
+    """slice_rows_exact with fixed_point_shift; any S, moderate sizes."""
+    m, k = A.shape
+    out = np.zeros((S, m, k), dtype=np.int8)
+    for i in range(m):
+        er = int(eA[i])
+        for l in range(k):
+            out[:, i, l] = remap_unsigned_to_signed(fixed_point_shift(float(A[i, l]), er, S), S)
+    return out
+
+
 def slice_rows(A: np.ndarray, eA: np.ndarray, S: int) -> np.ndarray:
-    return slice_rows_int64(A, eA, S) if S <= 8 else slice_rows_exact(A, eA, S)
+    return slice_rows_int64(A, eA, S) if S <= 8 else slice_rows_bigint(A, eA, S)
 
 
 # --------------------------------------------------------------------------------------

@@ -1,0 +1,47 @@
+"""Builds the HIP library in-tree: csrc/*.hip -> liboz_mi355x.so (gfx950 only)."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "liboz_mi355x.so")
+SOURCES = ["oz_api.hip", "oz_scan.hip", "oz_esc.hip", "oz_slice.hip", "oz_gemm_i8.hip",
+           "oz_recompose.hip", "oz_dgemm_f64.hip"]
+# packed FP32 instructions are switched off for all device code (known-bad on the test machines)
+FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+
+
+def _compile(src: str, extra=()) -> str:
+    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+    noise = ("packed-fp32-ops", "is not a recognized feature")
+    for line in r.stderr.splitlines():
+        if line.strip() and not any(n in line for n in noise):
+            print(line, file=sys.stderr)
+    return obj
+
+
+def build_library(verbose: bool = True, extra=()) -> str:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+    if verbose:
+        print("built", LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    build_library(extra=sys.argv[1:])

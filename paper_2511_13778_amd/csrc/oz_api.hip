@@ -1,0 +1,318 @@
+// C ABI of the library (see include/ozdgemm.h): argument checking, workspace layout and the
+// fixed, data-independent sequence of kernel launches.  Every kernel is enqueued on every call;
+// the ones after the verdict read the device-resident record and return at once when they are
+// not selected, so no host-device synchronisation is needed to route a call
+// (paper: section "GPU-Resident Integration" and the flowchart of the GEMM decision process).
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "oz_internal.h"
+
+struct oz_handle {
+    int device;
+    oz_heuristic_t hm;
+    // stage timing
+    int prof_calls;       // calls still to be recorded
+    int prof_next;        // index of the next call to record
+    std::vector<hipEvent_t> events;   // (OZ_NUM_STAGES + 1) per recorded call
+};
+
+namespace {
+
+using namespace oz;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool parse_trans(char c, bool& t) {
+    if (c == 'N' || c == 'n') { t = false; return true; }
+    if (c == 'T' || c == 't') { t = true; return true; }
+    return false;
+}
+
+bool valid_opts(const oz_opts_t& o) {
+    if (o.mode < OZ_DYNAMIC || o.mode > OZ_NATIVE) return false;
+    if (o.target_bits < 1 || o.target_bits > 200) return false;
+    if (o.max_bits < 1 || o.max_bits > 200) return false;
+    if (o.slices < 0 || o.slices > kMaxSlices) return false;
+    if (o.esc_block < 0 || o.esc_block > 1024 || o.esc_block % 16 != 0) return false;
+    if (o.heuristic != 0 && o.heuristic != 1) return false;
+    return true;
+}
+
+bool emulation_slower(const oz_heuristic_t& hm, int S, int64_t m, int64_t n, int64_t k) {
+    const int64_t flops = 2 * m * n * k;
+    const int64_t pairs = int64_t(S) * (S + 1) / 2;
+    const int64_t stream = (8 + S) * (m * k + k * n) + (8 * int64_t(S) + 16) * m * n;
+    const int64_t t_emu = hm.fixed_ns + (flops / hm.int8_ops_per_ns) * pairs + stream / hm.bytes_per_ns;
+    const int64_t t_f64 = flops / hm.fp64_flops_per_ns;
+    return t_emu > t_f64;
+}
+
+// largest slice count a call with these options can select
+int slice_cap(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int64_t k) {
+    if (o.mode == OZ_NATIVE) return 1;
+    if (o.mode != OZ_DYNAMIC) {
+        int s = o.slices > 0 ? o.slices : (o.max_bits + 1 + 7) / 8;
+        return s < 1 ? 1 : (s > kMaxSlices ? kMaxSlices : s);
+    }
+    int s = (o.max_bits + 1 + kHeadroomBits + 7) / 8;
+    if (s > kMaxSlices) s = kMaxSlices;
+    if (o.heuristic)   // the cost model is monotone in S: beyond this the verdict is "slower"
+        while (s > 1 && emulation_slower(h.hm, s, m, n, k)) --s;
+    return s;
+}
+
+bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int64_t k, Problem& p) {
+    if (m < 0 || n < 0 || k < 0) return false;
+    if (m > (int64_t(1) << 24) || n > (int64_t(1) << 24) || k > (int64_t(1) << 24)) return false;
+    p.m = m; p.n = n; p.k = k;
+    p.mp = round_up(m > 0 ? m : 1, kRowPad);
+    p.np = round_up(n > 0 ? n : 1, kRowPad);
+    p.kp = round_up(k > 0 ? k : 1, kKPad);
+    p.s_cap = slice_cap(h, o, m, n, k);
+    p.kblk = k_block_length(p.s_cap);
+    p.nkb = int((p.kp + p.kblk - 1) / p.kblk);
+    p.esc_block = o.esc_block > 0 ? o.esc_block : kDefaultEscBlock;
+    p.G = int((p.k + p.esc_block - 1) / p.esc_block);
+    if (p.G < 1) p.G = 1;
+    return true;
+}
+
+void make_layout(const Problem& p, oz_layout_t& L) {
+    size_t off = 0;
+    L.mp = p.mp; L.np = p.np; L.kp = p.kp; L.s_cap = p.s_cap; L.nkb = p.nkb; L.kblk = p.kblk;
+    L.off_record = off; off = align_up(off + sizeof(Record));
+    L.off_eA = off; off = align_up(off + size_t(p.mp) * 4);
+    L.off_eB = off; off = align_up(off + size_t(p.np) * 4);
+    // block tables (not part of the published layout)
+    off = align_up(off + size_t(2) * p.G * p.mp * 2);
+    off = align_up(off + size_t(2) * p.G * p.np * 2);
+    L.off_As = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.mp);
+    L.off_Bs = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.np);
+    L.off_P = off; off = align_up(off + size_t(p.nkb) * p.s_cap * p.np * p.mp * 4);
+    L.total_bytes = off;
+}
+
+Workspace bind(void* base, const Problem& p, const oz_layout_t& L) {
+    uint8_t* b = static_cast<uint8_t*>(base);
+    Workspace w;
+    w.rec = reinterpret_cast<Record*>(b + L.off_record);
+    w.eA = reinterpret_cast<int32_t*>(b + L.off_eA);
+    w.eB = reinterpret_cast<int32_t*>(b + L.off_eB);
+    size_t offU = align_up(L.off_eB + size_t(p.np) * 4);
+    size_t offV = align_up(offU + size_t(2) * p.G * p.mp * 2);
+    w.U = reinterpret_cast<int16_t*>(b + offU);
+    w.V = reinterpret_cast<int16_t*>(b + offV);
+    w.As = reinterpret_cast<int8_t*>(b + L.off_As);
+    w.Bs = reinterpret_cast<int8_t*>(b + L.off_Bs);
+    w.P = reinterpret_cast<int32_t*>(b + L.off_P);
+    return w;
+}
+
+bool check_dims(bool ta, bool tb, int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb, int64_t ldc) {
+    const int64_t rows_a = ta ? k : m, rows_b = tb ? n : k;
+    if (lda < (rows_a > 1 ? rows_a : 1)) return false;
+    if (ldb < (rows_b > 1 ? rows_b : 1)) return false;
+    if (ldc < (m > 1 ? m : 1)) return false;
+    return true;
+}
+
+// records the event closing stage `stage` of the profiled call, if profiling is active
+struct StageClock {
+    oz_handle* h;
+    hipStream_t st;
+    hipEvent_t* ev;
+    StageClock(oz_handle* hh, hipStream_t s) : h(hh), st(s), ev(nullptr) {
+        if (h->prof_calls > 0 && size_t(h->prof_next + 1) * (OZ_NUM_STAGES + 1) <= h->events.size()) {
+            ev = &h->events[size_t(h->prof_next) * (OZ_NUM_STAGES + 1)];
+            --h->prof_calls;
+            ++h->prof_next;
+            (void)hipEventRecord(ev[0], st);
+        }
+    }
+    void done(int stage) { if (ev) (void)hipEventRecord(ev[stage + 1], st); }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* oz_status_string(oz_status_t s) {
+    switch (s) {
+        case OZ_OK: return "ok";
+        case OZ_ERR_ARG: return "invalid argument";
+        case OZ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case OZ_ERR_DEVICE: return "device is not gfx950 or cannot be used";
+        case OZ_ERR_HIP: return "HIP runtime call failed";
+    }
+    return "unknown status";
+}
+
+void oz_default_opts(oz_opts_t* o) {
+    if (!o) return;
+    o->mode = OZ_DYNAMIC;
+    o->target_bits = 53;
+    o->max_bits = 200;
+    o->slices = 0;
+    o->esc_block = 0;
+    o->heuristic = 1;
+}
+
+oz_status_t oz_create(oz_handle_t* handle, int device) {
+    if (!handle) return OZ_ERR_ARG;
+    *handle = nullptr;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return OZ_ERR_DEVICE;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return OZ_ERR_DEVICE;
+    oz_handle* h = new (std::nothrow) oz_handle();
+    if (!h) return OZ_ERR_ARG;
+    h->device = device;
+    // measured on MI355X: slice GEMM rate, native FP64 GEMM rate, streaming rate, launch overhead
+    h->hm.int8_ops_per_ns = 2500000;
+    h->hm.fp64_flops_per_ns = 60000;
+    h->hm.bytes_per_ns = 4000;
+    h->hm.fixed_ns = 60000;
+    h->prof_calls = 0;
+    h->prof_next = 0;
+    *handle = h;
+    return OZ_OK;
+}
+
+oz_status_t oz_destroy(oz_handle_t h) {
+    if (!h) return OZ_ERR_ARG;
+    for (hipEvent_t e : h->events) (void)hipEventDestroy(e);
+    delete h;
+    return OZ_OK;
+}
+
+oz_status_t oz_set_heuristic(oz_handle_t h, const oz_heuristic_t* model) {
+    if (!h || !model) return OZ_ERR_ARG;
+    if (model->int8_ops_per_ns <= 0 || model->fp64_flops_per_ns <= 0 || model->bytes_per_ns <= 0 ||
+        model->fixed_ns < 0)
+        return OZ_ERR_ARG;
+    h->hm = *model;
+    return OZ_OK;
+}
+
+oz_status_t oz_dgemm_layout(oz_handle_t h, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                            const oz_opts_t* opts, oz_layout_t* layout) {
+    bool ta, tb;
+    if (!h || !opts || !layout || !parse_trans(transa, ta) || !parse_trans(transb, tb)) return OZ_ERR_ARG;
+    if (!valid_opts(*opts)) return OZ_ERR_ARG;
+    Problem p;
+    if (!make_problem(*h, *opts, m, n, k, p)) return OZ_ERR_ARG;
+    make_layout(p, *layout);
+    return OZ_OK;
+}
+
+size_t oz_dgemm_workspace_bytes(oz_handle_t h, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                const oz_opts_t* opts) {
+    oz_layout_t L;
+    if (oz_dgemm_layout(h, transa, transb, m, n, k, opts, &L) != OZ_OK) return 0;
+    return L.total_bytes;
+}
+
+oz_status_t oz_profile_enable(oz_handle_t h, int32_t max_calls) {
+    if (!h || max_calls < 0 || max_calls > 4096) return OZ_ERR_ARG;
+    const size_t need = size_t(max_calls) * (OZ_NUM_STAGES + 1);
+    while (h->events.size() < need) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return OZ_ERR_HIP;
+        h->events.push_back(e);
+    }
+    h->prof_calls = max_calls;
+    h->prof_next = 0;
+    return OZ_OK;
+}
+
+oz_status_t oz_profile_read(oz_handle_t h, int32_t call, float* stage_ms) {
+    if (!h || !stage_ms || call < 0 || call >= h->prof_next) return OZ_ERR_ARG;
+    hipEvent_t* ev = &h->events[size_t(call) * (OZ_NUM_STAGES + 1)];
+    for (int s = 0; s < OZ_NUM_STAGES; ++s) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev[s], ev[s + 1]) != hipSuccess) return OZ_ERR_HIP;
+        stage_ms[s] = ms;
+    }
+    return OZ_OK;
+}
+
+oz_status_t oz_native_dgemm(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n,
+                            int64_t k, double alpha, const double* A, int64_t lda, const double* B,
+                            int64_t ldb, double beta, double* C, int64_t ldc) {
+    bool ta, tb;
+    if (!h || !parse_trans(transa, ta) || !parse_trans(transb, tb)) return OZ_ERR_ARG;
+    if (m < 0 || n < 0 || k < 0 || !check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
+    if (m == 0 || n == 0) return OZ_OK;
+    if (!C || (k > 0 && alpha != 0.0 && (!A || !B))) return OZ_ERR_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (k == 0 || alpha == 0.0) launch_scale_c(st, m, n, beta, C, ldc);
+    else launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+    return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+}
+
+oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                     double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                     double* C, int64_t ldc, const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
+                     oz_result_t* result) {
+    bool ta, tb;
+    if (!h || !opts || !parse_trans(transa, ta) || !parse_trans(transb, tb)) return OZ_ERR_ARG;
+    if (!valid_opts(*opts)) return OZ_ERR_ARG;
+    Problem p;
+    if (!make_problem(*h, *opts, m, n, k, p)) return OZ_ERR_ARG;
+    if (!check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
+    if (m == 0 || n == 0) return OZ_OK;
+    if (!C) return OZ_ERR_ARG;
+    oz_layout_t L;
+    make_layout(p, L);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < L.total_bytes)
+        return OZ_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Workspace w = bind(workspace, p, L);
+    StageClock clk(h, st);
+
+    if (k == 0 || alpha == 0.0) {
+        // BLAS convention: nothing to multiply
+        launch_verdict(st, w, p, *opts, h->hm, 2, result);
+        launch_scale_c(st, m, n, beta, C, ldc);
+        for (int s = 0; s < OZ_NUM_STAGES; ++s) clk.done(s);
+        return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+    }
+    if (!A || !B) return OZ_ERR_ARG;
+
+    // element (r, l) of op(A) (r = i) and of op(B) (r = j) at base[r*stride_r + l*stride_l]
+    const int64_t a_sr = ta ? lda : 1, a_sl = ta ? 1 : lda;
+    const int64_t b_sr = tb ? 1 : ldb, b_sl = tb ? ldb : 1;
+
+    if (opts->mode == OZ_NATIVE) {
+        launch_verdict(st, w, p, *opts, h->hm, 0, result);
+        for (int s = 0; s <= 5; ++s) clk.done(s);
+        launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+        clk.done(6);
+        return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+    }
+
+    const bool guarded = opts->mode != OZ_FIXED_UNGUARDED;
+    launch_init(st, w, p);
+    launch_scan(st, A, a_sr, a_sl, m, p.mp, p, w.U, /*max_first=*/true, w.eA, w.rec, guarded);
+    launch_scan(st, B, b_sr, b_sl, n, p.np, p, w.V, /*max_first=*/false, w.eB, w.rec, guarded);
+    clk.done(0);
+    if (guarded) launch_esc(st, w, p);
+    clk.done(1);
+    launch_verdict(st, w, p, *opts, h->hm, guarded ? 1 : 0, result);
+    clk.done(2);
+    launch_slice(st, A, a_sr, a_sl, m, p.mp, p, w.eA, w.As, w.rec);
+    launch_slice(st, B, b_sr, b_sl, n, p.np, p, w.eB, w.Bs, w.rec);
+    clk.done(3);
+    launch_gemm_i8(st, w, p);
+    clk.done(4);
+    launch_recompose(st, w, p, alpha, beta, C, ldc);
+    clk.done(5);
+    if (guarded) launch_dgemm_f64(st, w.rec, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+    clk.done(6);
+    return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+}
+
+}  // extern "C"

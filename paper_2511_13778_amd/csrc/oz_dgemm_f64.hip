@@ -1,0 +1,138 @@
+// Native FP64 GEMM on the FP64 matrix instruction: the path the guard falls back to.
+// (paper: sections "Pre-processing and Safety Checks" and "Heuristic run time Selection":
+//  Inf/NaN in the inputs, an exponent span beyond the available bits, or a slice count outside
+//  the efficient range route the call to the native FP64 GEMM.)
+//
+//   C = alpha * op(A) * op(B) + beta * C,  ordinary floating-point accumulation over k.
+//
+// v_mfma_f64_16x16x4_f64; 128x128 tile per workgroup, 4 waves of 64x64 (4x4 MFMA tiles),
+// K step 16 through double-buffered LDS.  op(B) feeds the row operand and op(A) the column
+// operand so that the result's lane index runs along i and stores to column-major C coalesce.
+// The kernel is launched on every call and returns at once unless the verdict selected it.
+#include "oz_internal.h"
+
+namespace oz {
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+constexpr int kDM = 128, kDN = 128, kDK = 16;
+constexpr int kDPad = 4;                        // doubles of padding per LDS row
+constexpr int kDLd = kDM + kDPad;
+
+// tile loader: 16 (k) x 128 (r) elements of an operand whose element (r, l) is at
+// base[r*stride_r + l*stride_l]; out-of-range elements are zero.  8 values per thread.
+template <bool ROWS_CONTIG>
+__device__ __forceinline__ void dg_load(double (&v)[8], const double* __restrict__ X, int64_t stride_r,
+                                        int64_t stride_l, int64_t r0, int64_t rows, int64_t l0, int64_t k) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        int rr, ll;
+        if (ROWS_CONTIG) { rr = threadIdx.x & 127; ll = (threadIdx.x >> 7) + 2 * q; }
+        else { ll = threadIdx.x & 15; rr = (threadIdx.x >> 4) + 16 * q; }
+        const int64_t r = r0 + rr, l = l0 + ll;
+        v[q] = (r < rows && l < k) ? X[r * stride_r + l * stride_l] : 0.0;
+    }
+}
+template <bool ROWS_CONTIG>
+__device__ __forceinline__ void dg_store(const double (&v)[8], double* lds) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        int rr, ll;
+        if (ROWS_CONTIG) { rr = threadIdx.x & 127; ll = (threadIdx.x >> 7) + 2 * q; }
+        else { ll = threadIdx.x & 15; rr = (threadIdx.x >> 4) + 16 * q; }
+        lds[ll * kDLd + rr] = v[q];
+    }
+}
+
+template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG>
+__global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
+    const Record* rec, int64_t m, int64_t n, int64_t k, double alpha, const double* __restrict__ A,
+    int64_t a_sr, int64_t a_sl, const double* __restrict__ B, int64_t b_sr, int64_t b_sl, double beta,
+    double* __restrict__ C, int64_t ldc, int ntm) {
+    __shared__ double At[2][kDK * kDLd];
+    __shared__ double Bt[2][kDK * kDLd];
+    if (rec && !rec->res.fallback) return;
+
+    const int64_t i0 = int64_t(blockIdx.x % ntm) * kDM, j0 = int64_t(blockIdx.x / ntm) * kDN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wi = wave & 1, wj = wave >> 1;
+
+    v4d acc[4][4];   // [fj][fi]
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
+
+    double va[8], vb[8];
+    dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, 0, k);
+    dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, 0, k);
+    dg_store<A_ROWS_CONTIG>(va, At[0]);
+    dg_store<B_ROWS_CONTIG>(vb, Bt[0]);
+    __syncthreads();
+
+    int buf = 0;
+    for (int64_t l0 = 0; l0 < k; l0 += kDK) {
+        const bool have_next = l0 + kDK < k;
+        if (have_next) {
+            dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
+            dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
+        }
+        const double* la = At[buf] + wi * 64 + (lane & 15);
+        const double* lb = Bt[buf] + wj * 64 + (lane & 15);
+#pragma unroll
+        for (int kk = 0; kk < kDK / 4; ++kk) {
+            const int kr = (kk * 4 + (lane >> 4)) * kDLd;
+            double fa[4], fb[4];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) { fa[f] = la[kr + f * 16]; fb[f] = lb[kr + f * 16]; }
+#pragma unroll
+            for (int fj = 0; fj < 4; ++fj)
+#pragma unroll
+                for (int fi = 0; fi < 4; ++fi)
+                    acc[fj][fi] = __builtin_amdgcn_mfma_f64_16x16x4f64(fb[fj], fa[fi], acc[fj][fi], 0, 0, 0);
+        }
+        if (have_next) {
+            dg_store<A_ROWS_CONTIG>(va, At[buf ^ 1]);
+            dg_store<B_ROWS_CONTIG>(vb, Bt[buf ^ 1]);
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // result register r of tile (fj, fi): j = fj*16 + 4*r + lane/16, i = fi*16 + lane%16
+#pragma unroll
+    for (int fj = 0; fj < 4; ++fj)
+#pragma unroll
+        for (int fi = 0; fi < 4; ++fi)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t j = j0 + wj * 64 + fj * 16 + 4 * r + (lane >> 4);
+                const int64_t i = i0 + wi * 64 + fi * 16 + (lane & 15);
+                if (i < m && j < n) {
+                    double out = __dmul_rn(alpha, acc[fj][fi][r]);
+                    if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
+                    C[j * ldc + i] = out;
+                }
+            }
+}
+
+void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64_t m, int64_t n, int64_t k,
+                      double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                      double* C, int64_t ldc) {
+    // op(A)(i,l): N -> A[i + l*lda] (rows contiguous), T -> A[l + i*lda]
+    // op(B)(l,j): N -> B[l + j*ldb] (k contiguous),    T -> B[j + l*ldb] (rows contiguous)
+    const int64_t a_sr = ta ? lda : 1, a_sl = ta ? 1 : lda;
+    const int64_t b_sr = tb ? 1 : ldb, b_sl = tb ? ldb : 1;
+    const int ntm = int((m + kDM - 1) / kDM), ntn = int((n + kDN - 1) / kDN);
+    const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
+    const bool ac = !ta, bc = tb;
+#define OZ_DG(AC, BC) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC>), grid, block, 0, st, rec, m, n, k, alpha, A, \
+                                         a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm)
+    if (ac && bc) OZ_DG(true, true);
+    else if (ac && !bc) OZ_DG(true, false);
+    else if (!ac && bc) OZ_DG(false, true);
+    else OZ_DG(false, false);
+#undef OZ_DG
+}
+
+}  // namespace oz

@@ -1,0 +1,90 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ozdgemm.h"
+
+namespace oz {
+
+// ---- constants of the method -----------------------------------------------------------
+constexpr int kHeadroomBits = 1;      // spare bit in the leading digit: |X| < 2^(8S-2)
+constexpr int kMaxSlices = 26;        // 200 mantissa bits
+constexpr int kEscCap = 4096;         // reported ESC is clamped to this
+constexpr int kDefaultEscBlock = 64;
+
+// Exponents are kept as int16 in the block tables.  Real exponents lie in [-1074, 1023].
+// kExpZeroInMin: Min of a block that holds a zero (exp(0) = -infinity).
+// kExpAllZero  : Max and Min of a block without any non-zero entry.
+// Sums of two table entries classify a candidate: >= -4096 a real exponent sum,
+// [-10000, -4096) "no information", < -10000 "this block contributes nothing to the product".
+constexpr int kExpZeroInMin = -6144;
+constexpr int kExpAllZero = -12288;
+constexpr int kSumRealFloor = -4096;
+constexpr int kSumDeadBelow = -10000;
+
+// ---- tiling constants shared between kernels and the workspace layout --------------------
+constexpr int kRowPad = 256;          // rows of the slice panels are padded to this
+constexpr int kKPad = 128;            // k is padded to this (K tile of the INT8 GEMM)
+constexpr int kChunk = 16;            // bytes of k stored contiguously per row ("k chunk")
+
+// ---- device-resident control record ---------------------------------------------------
+struct Record {
+    int32_t infnan;        // set by the scan kernels (atomicOr)
+    int32_t span_max;      // max_ij (eA_i + eB_j - zt_ij), set by the ESC kernel (atomicMax)
+    oz_result_t res;       // written by the verdict kernel, read by every later kernel
+};
+
+struct Problem {
+    int64_t m, n, k;
+    int64_t mp, np, kp;    // padded sizes
+    int32_t s_cap;         // slice planes the workspace holds
+    int32_t nkb;           // number of k-blocks (int32 accumulator headroom)
+    int64_t kblk;          // k-block length (multiple of kKPad)
+    int32_t esc_block;     // b
+    int32_t G;             // ceil(k / b)
+};
+
+struct Workspace {
+    Record* rec;
+    int32_t* eA;           // [mp]
+    int32_t* eB;           // [np]
+    int16_t* U;            // [2G][mp]  h <  G: Max exponent of block h of row i of op(A)
+                           //           h >= G: Min exponent of block h-G
+    int16_t* V;            // [2G][np]  h <  G: Min exponent of block h of column j of op(B)
+                           //           h >= G: Max exponent of block h-G
+    int8_t* As;            // [s_cap][kp/16][mp][16]
+    int8_t* Bs;            // [s_cap][kp/16][np][16]
+    int32_t* P;            // [nkb][s_cap][np][mp]
+};
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// k-range one int32 accumulator can take: |digit product| <= 2^14 and an anti-diagonal sums at
+// most S*kblk of them; multiple of 256.
+inline int64_t k_block_length(int S) { return ((int64_t(1) << 17) - 1) / S / 256 * 256; }
+
+// ---- stage launchers (each only enqueues) --------------------------------------------
+// element (r, l) of a k-by-rows operand is at base[r*stride_r + l*stride_l]
+void launch_init(hipStream_t st, const Workspace& w, const Problem& p);
+void launch_scan(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l,
+                 int64_t rows, int64_t rows_p, const Problem& p, int16_t* tab, bool max_first,
+                 int32_t* e_out, Record* rec, bool check_infnan);
+void launch_esc(hipStream_t st, const Workspace& w, const Problem& p);
+// kind: 0 unguarded, 1 guarded, 2 nothing to multiply (record says "emulated, 0 slices")
+void launch_verdict(hipStream_t st, const Workspace& w, const Problem& p, const oz_opts_t& o,
+                    const oz_heuristic_t& hm, int kind, oz_result_t* user_result);
+void launch_slice(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l,
+                  int64_t rows, int64_t rows_p, const Problem& p, const int32_t* e_row,
+                  int8_t* slices, const Record* rec);
+void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p);
+void launch_recompose(hipStream_t st, const Workspace& w, const Problem& p, double alpha,
+                      double beta, double* C, int64_t ldc);
+// rec == nullptr: run unconditionally; otherwise run only when rec->res.fallback != 0
+void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64_t m, int64_t n,
+                      int64_t k, double alpha, const double* A, int64_t lda, const double* B,
+                      int64_t ldb, double beta, double* C, int64_t ldc);
+void launch_scale_c(hipStream_t st, int64_t m, int64_t n, double beta, double* C, int64_t ldc);
+
+}  // namespace oz

@@ -1,0 +1,81 @@
+// FP64 recomposition of the integer anti-diagonal sums and the alpha/beta update.
+// (paper: section "FP64 Emulation on Low-Precision Units": slice products are recombined;
+//  section "Pre-processing and Safety Checks", second half: partial results are aggregated
+//  before the terminal conversion to FP64, so an Inf can only appear in that last step.)
+//
+//   AB_ij = 2^(eA_i + eB_j - 10) * sum_kb sum_d 256^-d P[kb][d][j][i]
+//   C_ij  = alpha * AB_ij + beta * C_ij           (C not read when beta == 0)
+//
+// Order (fixed, so results are reproducible): k-blocks ascending; inside a k-block Horner from
+// the least significant anti-diagonal, R <- P_d + R * 2^-8; block results added unscaled; the
+// power of two applied last with ldexp; alpha*AB and beta*C rounded separately, then added.
+// HBM-bound: 4*S*nkb bytes read and 8 (+8 when beta != 0) bytes moved per element of C.
+#include "oz_internal.h"
+
+namespace oz {
+
+constexpr int kRecElemsPerThread = 4;
+
+__global__ __launch_bounds__(256) void recompose_kernel(const int32_t* __restrict__ P,
+                                                        const int32_t* __restrict__ eA,
+                                                        const int32_t* __restrict__ eB, int64_t m,
+                                                        int64_t mp, int64_t np, int64_t kp, int s_cap,
+                                                        double alpha, double beta,
+                                                        double* __restrict__ C, int64_t ldc,
+                                                        const Record* rec) {
+    if (rec->res.fallback) return;
+    const int S = rec->res.slices_used;
+    const int64_t kblk = ((int64_t(1) << 17) - 1) / S / 256 * 256;
+    const int nkb = int((kp + kblk - 1) / kblk);
+    const int64_t j = blockIdx.y;
+    const int eb = eB[j];
+    const int64_t plane = np * mp;
+#pragma unroll
+    for (int q = 0; q < kRecElemsPerThread; ++q) {
+        const int64_t i = (int64_t(blockIdx.x) * kRecElemsPerThread + q) * 256 + threadIdx.x;
+        if (i >= m) continue;
+        const int32_t* p = P + j * mp + i;
+        double R = 0.0;
+        for (int kb = 0; kb < nkb; ++kb) {
+            double Rb = 0.0;
+            for (int d = S - 1; d >= 0; --d)
+                Rb = double(p[(int64_t(kb) * s_cap + d) * plane]) + Rb * 0x1p-8;
+            R = R + Rb;
+        }
+        const int ea = eA[i];
+        const int sc = (ea > kExpAllZero ? ea : 0) + (eb > kExpAllZero ? eb : 0) + (2 * kHeadroomBits - 12);
+        const double ab = ldexp(R, sc);
+        double out = __dmul_rn(alpha, ab);
+        if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
+        C[j * ldc + i] = out;
+    }
+}
+
+// C = beta * C (beta == 0 stores zeros without reading C)
+__global__ __launch_bounds__(256) void scale_c_kernel(int64_t m, double beta, double* __restrict__ C,
+                                                      int64_t ldc) {
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t j = blockIdx.y;
+    if (i >= m) return;
+    C[j * ldc + i] = (beta == 0.0) ? 0.0 : __dmul_rn(beta, C[j * ldc + i]);
+}
+
+void launch_recompose(hipStream_t st, const Workspace& w, const Problem& p, double alpha, double beta,
+                      double* C, int64_t ldc) {
+    const unsigned gx = unsigned((p.m + 256 * kRecElemsPerThread - 1) / (256 * kRecElemsPerThread));
+    for (int64_t j0 = 0; j0 < p.n; j0 += 65535) {
+        const unsigned gy = unsigned(p.n - j0 < 65535 ? p.n - j0 : 65535);
+        hipLaunchKernelGGL(recompose_kernel, dim3(gx, gy), dim3(256), 0, st, w.P + j0 * p.mp, w.eA, w.eB + j0,
+                           p.m, p.mp, p.np, p.kp, p.s_cap, alpha, beta, C + j0 * ldc, ldc, w.rec);
+    }
+}
+
+void launch_scale_c(hipStream_t st, int64_t m, int64_t n, double beta, double* C, int64_t ldc) {
+    const unsigned gx = unsigned((m + 255) / 256);
+    for (int64_t j0 = 0; j0 < n; j0 += 65535) {
+        const unsigned gy = unsigned(n - j0 < 65535 ? n - j0 : 65535);
+        hipLaunchKernelGGL(scale_c_kernel, dim3(gx, gy), dim3(256), 0, st, m, beta, C + j0 * ldc, ldc);
+    }
+}
+
+}  // namespace oz

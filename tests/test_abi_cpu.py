@@ -1,0 +1,61 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports every symbol that
+include/ozdgemm.h declares; the calls that do not touch a device behave."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2511_13778_amd import ozdgemm as g
+    if not os.path.exists(g.LIB_PATH):
+        from paper_2511_13778_amd.build import build_library
+        build_library(verbose=False)
+    return g, g.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ozdgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(oz_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    g, dll = lib
+    names = declared_functions()
+    assert set(names) == set(g.EXPORTS), names
+    for name in names:
+        assert getattr(dll, name) is not None
+
+
+def test_struct_sizes_match_header(lib):
+    g, _ = lib
+    assert C.sizeof(g.oz_opts_t) == 24
+    assert C.sizeof(g.oz_result_t) == 24
+    assert C.sizeof(g.oz_heuristic_t) == 32
+    assert C.sizeof(g.oz_layout_t) == 6 * 8 + 7 * C.sizeof(C.c_size_t)
+
+
+def test_host_only_calls(lib):
+    g, dll = lib
+    o = g.oz_opts_t()
+    dll.oz_default_opts(C.byref(o))
+    assert (o.mode, o.target_bits, o.max_bits, o.slices, o.esc_block, o.heuristic) == (0, 53, 200, 0, 0, 1)
+    assert dll.oz_status_string(0) == b"ok"
+    assert b"workspace" in dll.oz_status_string(2)
+    # null handle / null pointers are argument errors, not crashes
+    assert dll.oz_destroy(None) == 1
+    assert dll.oz_create(None, 0) == 1
+    assert dll.oz_dgemm_workspace_bytes(None, b"N", b"N", 8, 8, 8, C.byref(o)) == 0
+    assert dll.oz_profile_enable(None, 4) == 1
+
+
+def test_no_cpu_fallback_in_binding():
+    # the product path must not import the oracle
+    for name in ("ozdgemm.py", "build.py", "workloads.py", "__init__.py"):
+        src = open(os.path.join(ROOT, "paper_2511_13778_amd", name)).read()
+        assert "oracle" not in src.replace("CPU oracle's tests", ""), name

@@ -1,0 +1,326 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: bit-exact for row/column exponents, ESC, slice count, fallback flag, slices (int8) and
+anti-diagonal products (int32); final C within k*2^-53 * (|alpha||A||B| + |beta||C|)
+componentwise of the exact reference, and (because the library uses the oracle's summation
+order) also bit-identical to the oracle's C on the emulated path.
+"""
+import numpy as np
+import pytest
+
+from oracle import exact as ex
+from oracle import ozaki as oz
+from paper_2511_13778_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2511_13778_amd import ozdgemm as g
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
+    h = g.Handle(0)
+    yield g, h
+    h.close()
+
+
+def run_gpu(g, h, A, B, alpha=1.0, beta=0.0, Cin=None, transa="N", transb="N", pad=0, **opt):
+    """Runs oz_dgemm on logical A (m x k), B (k x n); returns (C, Gemm object, Result)."""
+    m, k = A.shape
+    n = B.shape[1]
+    opts = g.make_opts(**opt)
+    gm = g.Gemm(h, m, n, k, opts, transa, transb)
+
+    def dev(X, trans):
+        # column-major storage of X (or of X^T when trans), leading dimension padded by `pad`
+        S = X.T if trans == "T" else X
+        rows, cols = S.shape
+        ld = max(1, rows) + pad
+        buf = np.full((cols, ld), 7.25)           # padding holds junk that must never be read as data
+        buf[:, :rows] = S.T
+        return torch.from_numpy(buf).cuda(), ld
+
+    dA, lda = dev(A, transa)
+    dB, ldb = dev(B, transb)
+    ldc = max(1, m) + pad
+    cbuf = np.full((n, ldc), np.nan)              # NaN: proves C is not read when beta == 0
+    if Cin is not None:
+        cbuf[:, :m] = Cin.T
+    dC = torch.from_numpy(cbuf).cuda()
+    gm.run(dA, lda, dB, ldb, dC, ldc, alpha, beta)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    if pad:
+        assert np.all(np.isnan(out[:, m:])), "wrote outside the m x n window of C"
+    return out[:, :m].T.copy(), gm, gm.result()
+
+
+MODES = {"dynamic": oz.MODE_DYNAMIC, "forced": oz.MODE_FORCED_GUARDED, "fixed_guarded": oz.MODE_FIXED_GUARDED,
+         "unguarded": oz.MODE_FIXED_UNGUARDED, "native": oz.MODE_NATIVE}
+
+
+def check_against_oracle(g, h, A, B, alpha=1.0, beta=0.0, Cin=None, mode="forced", target_bits=53,
+                         max_bits=55, slices=0, esc_block=0, transa="N", transb="N", pad=0, bound=True,
+                         intermediates=True):
+    m, k = A.shape
+    n = B.shape[1]
+    got, gm, res = run_gpu(g, h, A, B, alpha, beta, Cin, transa, transb, pad, mode=MODES[mode],
+                           target_bits=target_bits, max_bits=max_bits, slices=slices, esc_block=esc_block,
+                           heuristic=0)
+    tr = oz.emulated_dgemm(A, B, alpha, beta, Cin, mode=MODES[mode], target_bits=target_bits,
+                           max_bits=max_bits, slices=slices, esc_block=esc_block or oz.DEFAULT_ESC_BLOCK)
+    v = tr.verdict
+    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan) == \
+           (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan)
+    if not v.fallback:
+        S = v.slices_used
+        if intermediates:
+            eA, eB = gm.row_exponents()
+            np.testing.assert_array_equal(eA, np.where(tr.eA > oz.NEG_INF_BELOW, tr.eA, -12288))
+            np.testing.assert_array_equal(eB, np.where(tr.eB > oz.NEG_INF_BELOW, tr.eB, -12288))
+            As, Bs = gm.slices(S)
+            np.testing.assert_array_equal(As, tr.As)
+            np.testing.assert_array_equal(Bs, tr.Bs)
+            np.testing.assert_array_equal(gm.products(S, tr.P.shape[0]), tr.P)
+        np.testing.assert_array_equal(got, tr.C)          # same summation order: bit-identical
+    if bound:
+        idx = [(i, j) for i in range(m) for j in range(n)]
+        exact = ex.exact_entries(A, B, idx, alpha, beta, Cin).reshape(m, n)
+        den = ex.bound_denominator(A, B, None, alpha, beta, Cin)
+        assert ex.gradeA_ratio(got, exact, den, k) <= 1.0
+    return got, res, tr
+
+
+def test_config1_128_cubed(lib):
+    g, h = lib
+    A, B = wl.uniform_pm1(128, 128, 128, seed=1)
+    for mode in ("unguarded", "forced"):
+        _, res, _ = check_against_oracle(g, h, A, B, mode=mode, max_bits=55)
+        assert res.slices_used == 7 and res.fallback == 0
+
+
+def test_ragged_multi_tile_dynamic(lib):
+    # several 256-tiles in both directions, ragged tails in m, n and k
+    g, h = lib
+    A, B, Cin = wl.lognormal_spread(300, 777, 520, 1.0, seed=3, with_c=True)
+    _, res, _ = check_against_oracle(g, h, A, B, 1.5, 0.5, Cin, mode="dynamic", max_bits=200, pad=3)
+    assert res.fallback == 0 and res.slices_used >= 8
+
+
+@pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
+def test_transposes(lib, ta, tb):
+    g, h = lib
+    A, B = wl.lognormal_spread(130, 200, 260, 0.5, seed=11)
+    check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, transa=ta, transb=tb, pad=5)
+
+
+def test_int32_k_blocking(lib):
+    # S = 7 takes 18688 k per int32 accumulator: 19000 needs two k-blocks
+    g, h = lib
+    A, B = wl.uniform_pm1(40, 19000, 24, seed=12)
+    _, res, tr = check_against_oracle(g, h, A, B, mode="unguarded", max_bits=55, bound=False)
+    assert tr.P.shape[0] == 2
+    idx = [(i, j) for i in range(0, 40, 7) for j in range(0, 24, 5)]
+    exact = ex.exact_entries(A, B, idx)
+    den = ex.bound_denominator(A, B, idx)
+    got = np.array([_[i, j] for i, j in idx])
+    assert ex.gradeA_ratio(got, exact, den, 19000) <= 1.0
+
+
+def test_worst_case_digits_do_not_overflow_int32(lib):
+    # every digit of every slice at an extreme of its range, longest k-block
+    g, h = lib
+    S = 3
+    k = oz.k_block_length(S)
+    a = -4161664.0                  # q = 0: X = -63*65536 - 128*256 - 128, digits (-63, -128, -128)
+    A = np.full((4, k), a)
+    B = np.full((k, 4), a)
+    check_against_oracle(g, h, A, B, mode="unguarded", slices=S, bound=False)
+
+
+@pytest.mark.parametrize("S", [1, 2, 9, 12, 26])
+def test_slice_counts_beyond_64_bits(lib, S):
+    g, h = lib
+    rng = np.random.default_rng(S)
+    A = rng.standard_normal((20, 70)) * np.exp2(rng.integers(-30, 30, (20, 70)))
+    B = rng.standard_normal((70, 12)) * np.exp2(rng.integers(-30, 30, (70, 12)))
+    A[3, 5] = 5e-324
+    A[4, :] = np.ldexp(rng.uniform(-1, 1, 70), -1060)
+    check_against_oracle(g, h, A, B, mode="unguarded", slices=S, bound=False)
+
+
+def test_zeros_and_negative_zero(lib):
+    g, h = lib
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((70, 200))
+    B = rng.standard_normal((200, 90))
+    A[10, :] = 0.0                   # all-zero row
+    B[:, 20] = 0.0                   # all-zero column
+    A[:, 64:128] = 0.0               # a whole ESC block of zeros in every row
+    A[5, 3] = -0.0
+    B[7, 7] = -0.0
+    got, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200)
+    assert res.fallback == 0
+    assert np.all(got[10, :] == 0.0) and np.all(got[:, 20] == 0.0)
+    assert not np.any(np.signbit(got[10, :]))
+
+
+def test_denormal_inputs(lib):
+    # every entry of A denormal (true exponents from the leading bit, no implicit one); the
+    # product lands in the normal range again.  Slices and products must match the oracle; the
+    # result must be the exact product up to the usual bound.
+    g, h = lib
+    rng = np.random.default_rng(15)
+    A = np.ldexp(rng.uniform(-1, 1, (40, 96)), -1040)
+    A[0, 0] = 5e-324
+    B = np.ldexp(rng.uniform(-1, 1, (96, 30)), 900)
+    assert np.all(np.abs(A) < 2.3e-308)
+    got, res, _ = check_against_oracle(g, h, A, B, mode="forced", max_bits=55)
+    assert res.fallback == 0 and res.esc < 40
+
+
+def test_zero_blocks_identically_zero_product(lib):
+    g, h = lib
+    A = np.hstack([np.full((8, 64), 3.0), np.zeros((8, 64))])
+    B = np.vstack([np.zeros((64, 8)), np.full((64, 8), 5.0)])
+    got, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200)
+    assert res.esc == 1 and np.all(got == 0.0)
+    # one zero in each operand's only block: no candidate, ESC unbounded -> native path
+    A2 = np.ones((4, 64)); A2[:, 0] = 0.0
+    B2 = np.ones((64, 4)); B2[1, :] = 0.0
+    got, res, _ = check_against_oracle(g, h, A2, B2, mode="dynamic", max_bits=200)
+    assert (res.fallback, res.reason, res.esc) == (1, oz.REASON_BITS, oz.ESC_CAP)
+    assert np.all(got == 62.0)
+
+
+@pytest.mark.parametrize("b", [16, 128, 1024])
+def test_esc_block_lengths(lib, b):
+    g, h = lib
+    A, B = wl.lognormal_spread(64, 1100, 64, 1.5, seed=20 + b)
+    check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, esc_block=b, intermediates=False)
+
+
+def test_grading_test2_guardrails(lib):
+    g, h = lib
+    A, B, x = wl.grading_test2(96, 40, seed=2)
+    _, res, _ = check_against_oracle(g, h, A, B, mode="fixed_guarded", max_bits=55, bound=False)
+    assert (res.fallback, res.reason, res.esc) == (1, oz.REASON_BITS, 81)
+    _, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200)
+    assert res.fallback == 0 and res.slices_used == oz.slices_dynamic(53, 81)
+
+
+def test_adversarial_wide_span_falls_back(lib):
+    g, h = lib
+    A, B = wl.wide_span(260, 300, 130, seed=7)
+    got, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, bound=False)
+    assert (res.fallback, res.reason) == (1, oz.REASON_BITS) and res.esc > 600
+    idx = [(i, j) for i in range(0, 260, 37) for j in range(0, 130, 17)]
+    exact = ex.exact_entries(A, B, idx)
+    den = ex.bound_denominator(A, B, idx)
+    assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, 300) <= 1.0
+
+
+def test_adversarial_inf_nan_falls_back(lib):
+    g, h = lib
+    A0, B0 = wl.lognormal_spread(150, 260, 140, 0.5, seed=8)
+    A, B = wl.plant_inf_nan(A0, B0, seed=8)
+    got, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, bound=False)
+    assert (res.fallback, res.reason, res.infnan) == (1, oz.REASON_INFNAN, 1)
+    with np.errstate(all="ignore"):
+        ref = A @ B
+    np.testing.assert_array_equal(np.isnan(got), np.isnan(ref))
+    np.testing.assert_array_equal(np.isinf(got), np.isinf(ref))
+    fin = np.isfinite(ref)
+    assert np.allclose(got[fin], ref[fin], rtol=1e-10, atol=1e-10)
+    # forced mode also yields to Inf/NaN
+    _, res, _ = check_against_oracle(g, h, A, B, mode="forced", max_bits=55, bound=False)
+    assert res.reason == oz.REASON_INFNAN
+
+
+def test_adversarial_rank1_cancellation(lib):
+    g, h = lib
+    A, B = wl.rank1_cancel(200, 300, 100, seed=9)
+    _, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200)
+    assert res.fallback == 0 and res.slices_used >= 8
+
+
+def test_row_scaling_invariance(lib):
+    # config 4's structure: row i of A times 2^(i mod 40) leaves the digits unchanged and scales C exactly
+    g, h = lib
+    A, B, A0 = wl.row_scaled(128, 512, 64, seed=6)
+    got, _, tr = check_against_oracle(g, h, A, B, mode="forced", max_bits=55)
+    got0, _, tr0 = check_against_oracle(g, h, A0, B, mode="forced", max_bits=55)
+    np.testing.assert_array_equal(tr.As, tr0.As)
+    scale = np.ldexp(1.0, (np.arange(128) % 40).astype(np.int32))[:, None]
+    np.testing.assert_array_equal(got, got0 * scale)
+
+
+def test_emergent_infinity(lib):
+    g, h = lib
+    A = np.full((3, 8), 1.5e200)
+    B = np.full((8, 3), 1.2e200)
+    B[:, 1] *= -1
+    got, res, _ = check_against_oracle(g, h, A, B, mode="forced", max_bits=55, bound=False)
+    assert np.all(got[:, 0] == np.inf) and np.all(got[:, 1] == -np.inf)
+
+
+def test_degenerate_sizes(lib):
+    g, h = lib
+    Cin = np.arange(12.0).reshape(3, 4)
+    A, B = np.ones((3, 5)), np.ones((5, 4))
+    got, _, res = run_gpu(g, h, np.zeros((3, 0)), np.zeros((0, 4)), 1.0, 2.0, Cin, mode=g.OZ_DYNAMIC)
+    np.testing.assert_array_equal(got, 2 * Cin)
+    got, _, res = run_gpu(g, h, A, B, 0.0, 0.0, Cin, mode=g.OZ_DYNAMIC)
+    np.testing.assert_array_equal(got, np.zeros((3, 4)))
+    assert (res.fallback, res.slices_used, res.esc) == (0, 0, -1)
+    got, _, _ = run_gpu(g, h, np.ones((0, 5)), B, mode=g.OZ_DYNAMIC)      # m == 0: nothing happens
+    assert got.shape == (0, 4)
+    got, _, _ = run_gpu(g, h, np.full((1, 1), 3.0), np.full((1, 1), -2.0), mode=g.OZ_FORCED_GUARDED, max_bits=55)
+    assert got[0, 0] == -6.0
+
+
+def test_heuristic_sends_small_problems_native(lib):
+    g, h = lib
+    A, B = wl.uniform_pm1(48, 48, 48, seed=30)
+    got, _, res = run_gpu(g, h, A, B, mode=g.OZ_DYNAMIC, max_bits=200, heuristic=1)
+    assert (res.fallback, res.reason) == (1, oz.REASON_HEURISTIC)
+    v = oz.verdict(oz.MODE_DYNAMIC, 53, 200, 0, False, res.esc, 48, 48, 48, oz.HeuristicModel())
+    assert v.reason == oz.REASON_HEURISTIC
+    assert np.allclose(got, A @ B, rtol=0, atol=48 * 2.0 ** -53 * 48)
+
+
+@pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
+def test_native_fp64_gemm(lib, ta, tb):
+    g, h = lib
+    m, n, k = 200, 150, 333
+    A, B, Cin = wl.lognormal_spread(m, k, n, 0.5, seed=40, with_c=True)
+    got, _, res = run_gpu(g, h, A, B, 1.5, 0.5, Cin, ta, tb, pad=2, mode=g.OZ_NATIVE)
+    assert (res.fallback, res.reason) == (1, oz.REASON_NATIVE)
+    idx = [(i, j) for i in range(0, m, 13) for j in range(0, n, 11)]
+    exact = ex.exact_entries(A, B, idx, 1.5, 0.5, Cin)
+    den = ex.bound_denominator(A, B, idx, 1.5, 0.5, Cin)
+    assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
+
+
+def test_argument_errors(lib):
+    g, h = lib
+    opts = g.make_opts(mode=g.OZ_FORCED_GUARDED, max_bits=55)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    d = torch.zeros(64 * 64, dtype=torch.float64, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    need = h.workspace_bytes("N", "N", 64, 64, 64, opts)
+    assert need > 0
+    def call(ta="N", tb="N", m=64, n=64, k=64, lda=64, ldb=64, ldc=64, wsb=None, o=opts):
+        h.dgemm(st, ta, tb, m, n, k, 1.0, d.data_ptr(), lda, d.data_ptr(), ldb, 0.0, d.data_ptr(), ldc, o,
+                ws.data_ptr(), need if wsb is None else wsb)
+    for kw, status in (({"ta": "X"}, 1), ({"m": -1}, 1), ({"lda": 63}, 1), ({"ldb": 10}, 1), ({"ldc": 1}, 1),
+                       ({"wsb": need - 1}, 2), ({"o": g.make_opts(mode=9)}, 1),
+                       ({"o": g.make_opts(esc_block=24)}, 1), ({"o": g.make_opts(max_bits=500)}, 1)):
+        with pytest.raises(g.OzError) as e:
+            call(**kw)
+        assert e.value.status == status
+    assert h.workspace_bytes("N", "Q", 64, 64, 64, opts) == 0
+    torch.cuda.synchronize()

@@ -94,6 +94,19 @@ def test_enough_slices_are_exact():
         assert Fraction(X) == Fraction(float(a)) * Fraction(2) ** (8 * S - 3 - e_row)
 
 
+@pytest.mark.parametrize("S", [1, 7, 9, 26])
+def test_shift_route_matches_rationals(S):
+    rng = np.random.default_rng(70 + S)
+    v = np.concatenate([_edge_values(), rng.standard_normal(60) * np.exp2(rng.integers(-80, 80, 60))])
+    for e_extra in (0, 5, 300):
+        e_row = int(oz.exponents(v).max()) + e_extra
+        for a in v:
+            assert oz.fixed_point_shift(float(a), e_row, S) == oz.fixed_point(float(a), e_row, S)
+    A = v[:24].reshape(4, 6)
+    eA = oz.row_exponents(A)
+    np.testing.assert_array_equal(oz.slice_rows_bigint(A, eA, S), oz.slice_rows_exact(A, eA, S))
+
+
 @pytest.mark.parametrize("S", [1, 3, 7, 8])
 def test_vectorised_route_matches_big_integers(S):
     rng = np.random.default_rng(7 + S)
