@@ -65,24 +65,42 @@ def exact_dot_fsum(x: np.ndarray, y: np.ndarray, extra=()) -> float:
     return math.fsum(terms)
 
 
+def _int_parts(v: np.ndarray):
+    """v = M * 2^e elementwise with M an integer of at most 53 bits (object array) and e int."""
+    f, p = np.frexp(np.asarray(v, dtype=np.float64))
+    M = (f * 9007199254740992.0).astype(np.int64).astype(object)     # f * 2^53 is an exact integer
+    return M, p.astype(np.int64) - 53
+
+
+def exact_dot_fraction(x: np.ndarray, y: np.ndarray) -> Fraction:
+    """sum_l x_l*y_l as an exact rational, accumulated in Python integers:
+    each product is Mx*My * 2^(ex+ey); all are shifted to the smallest exponent and added."""
+    Mx, ex = _int_parts(x)
+    My, ey = _int_parts(y)
+    e = ex + ey
+    emin = int(e.min()) if len(e) else 0
+    total = int(np.sum((Mx * My) * (2 ** (e - emin).astype(object)), initial=0))
+    return Fraction(total) * Fraction(2) ** emin
+
+
 def exact_entries(A, B, idx, alpha=1.0, beta=0.0, C=None):
     """Correctly rounded alpha*(A*B)_ij + beta*C_ij for the sampled (i, j) in idx.
 
-    alpha is folded in exactly by scaling the row (alpha*a_il is split like any product only
-    when alpha is not a power of two; here alpha*x is carried as a second error-free product)."""
+    alpha == 1: every term is an error-free product, added by fsum.  Otherwise the dot product
+    is accumulated exactly in integers, combined with alpha and beta*C as rationals, and rounded
+    once by the conversion to float."""
     A = np.asarray(A, dtype=np.float64)
     B = np.asarray(B, dtype=np.float64)
     out = np.empty(len(idx), dtype=np.float64)
-    fa = Fraction(float(alpha))
+    fa, fb = Fraction(float(alpha)), Fraction(float(beta))
     for t, (i, j) in enumerate(idx):
         if alpha == 1.0:
             extra = [(beta, C[i, j])] if beta != 0.0 else []
             out[t] = exact_dot_fsum(A[i, :], B[:, j], extra)
         else:
-            s = sum((Fraction(float(a)) * Fraction(float(b)) for a, b in zip(A[i, :], B[:, j])), Fraction(0))
-            s = fa * s
+            s = fa * exact_dot_fraction(A[i, :], B[:, j])
             if beta != 0.0:
-                s += Fraction(float(beta)) * Fraction(float(C[i, j]))
+                s += fb * Fraction(float(C[i, j]))
             out[t] = float(s)          # Fraction -> float rounds correctly
     return out
 

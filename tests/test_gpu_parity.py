@@ -88,9 +88,12 @@ def check_against_oracle(g, h, A, B, alpha=1.0, beta=0.0, Cin=None, mode="forced
         np.testing.assert_array_equal(got, tr.C)          # same summation order: bit-identical
     if bound:
         idx = [(i, j) for i in range(m) for j in range(n)]
-        exact = ex.exact_entries(A, B, idx, alpha, beta, Cin).reshape(m, n)
-        den = ex.bound_denominator(A, B, None, alpha, beta, Cin)
-        assert ex.gradeA_ratio(got, exact, den, k) <= 1.0
+        if len(idx) > 6000:                       # exact reference on a seeded sample of the entries
+            pick = np.random.default_rng(m * 31 + n).choice(len(idx), 6000, replace=False)
+            idx = [idx[t] for t in pick]
+        exact = ex.exact_entries(A, B, idx, alpha, beta, Cin)
+        den = ex.bound_denominator(A, B, idx, alpha, beta, Cin)
+        assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
     return got, res, tr
 
 

@@ -80,6 +80,9 @@ def test_fsum_reference_matches_rationals():
     fr2 = ex.exact_gemm_fraction(A, B, 1.5, 0.5, C)
     got2 = ex.exact_entries(A, B, idx, 1.5, 0.5, C)
     assert all(got2[t] == float(fr2[i][j]) for t, (i, j) in enumerate(idx))
+    assert ex.exact_dot_fraction(A[1], B[:, 2]) == sum(
+        (Fraction(float(a)) * Fraction(float(b)) for a, b in zip(A[1], B[:, 2])), Fraction(0))
+    assert ex.exact_dot_fraction(np.array([5e-324, 3.0]), np.array([5e-324, -0.0])) == Fraction(5e-324) ** 2
     got3 = ex.exact_entries(A, B, idx, 1.0, 0.5, C)
     fr3 = ex.exact_gemm_fraction(A, B, 1.0, 0.5, C)
     assert all(got3[t] == float(fr3[i][j]) for t, (i, j) in enumerate(idx))
