@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--phi", type=float, default=1.0)
     ap.add_argument("--mode", default="forced", choices=["forced", "unguarded", "dynamic", "native"])
     ap.add_argument("--slices", type=int, default=0)
-    ap.add_argument("--cpu-size", type=int, default=2048)
+    ap.add_argument("--cpu-size", type=int, default=4096)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-native", action="store_true")
     args = ap.parse_args()
