@@ -10,15 +10,19 @@
 // anti-diagonals d; all pairs of one d accumulate into the same int32 registers (their k
 // ranges are simply concatenated), so only S tiles are written per k-block.
 //
-// Mapping to gfx950: v_mfma_i32_32x32x32_i8, 4 waves per workgroup, each wave a 128x128
-// sub-tile (4x4 MFMA tiles, 256 accumulator registers per lane).  K tile 128, LDS double
-// buffered (2 x 64 KB of the CU's 160 KB).  The slice panels are stored [k/16][row][16], so a
-// tile is a set of contiguous 4 KB runs in HBM and the LDS image [k chunk][row][16 B] is read
-// by the MFMA operand loads (one ds_read_b128 per lane: row = lane%32, k chunk = lane/32)
-// without bank conflicts.  The B-slices feed the MFMA's row operand and the A-slices its column
-// operand, so the lane index of the result runs along i and stores to P (i contiguous) coalesce.
-// Workgroup ids are remapped so that the tiles resident on one XCD form a compact block and
-// share their A and B panels in that XCD's L2.
+// Mapping to gfx950:
+//  * v_mfma_i32_32x32x32_i8; 4 waves per workgroup, each wave a 128x128 sub-tile (4x4 MFMA
+//    tiles, 256 accumulator registers per lane); one workgroup per CU.
+//  * K step 64 per pipeline stage; 4 LDS stages of 32 KB (128 of the CU's 160 KB).  Tiles go
+//    from HBM/L2 straight into LDS with global_load_lds_dwordx4 (no staging registers, no LDS
+//    store instructions), issued three stages ahead of their use; one workgroup barrier per
+//    stage.  The slice panels are stored [k/16][row][16], so a tile is four contiguous 4 KB
+//    runs per operand and the LDS image [k chunk][row][16 B] is what the MFMA operand loads
+//    read (ds_read_b128 per lane: row = lane%32, k chunk = lane/32) without bank conflicts.
+//  * The B-slices feed the MFMA's row operand and the A-slices its column operand, so the lane
+//    index of the result runs along i and the stores to P (i contiguous) coalesce.
+//  * Workgroup ids are remapped so that the tiles resident on one XCD form a compact block and
+//    share their A and B panels in that XCD's L2.
 #include "oz_internal.h"
 
 namespace oz {
@@ -28,9 +32,13 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kBM = 256;             // tile extent along i (rows of op(A))
 constexpr int kBN = 256;             // tile extent along j (columns of op(B))
-constexpr int kBK = kKPad;           // 128
-constexpr int kStageBytes = (kBM + kBN) * kBK;   // 64 KB
-constexpr int kGemmLds = 2 * kStageBytes;
+constexpr int kBK = 64;              // K step per pipeline stage (kKPad is a multiple)
+constexpr int kStages = 4;
+constexpr int kStageBytes = (kBM + kBN) * kBK;   // 32 KB
+constexpr int kGemmLds = kStages * kStageBytes;  // 128 KB
+constexpr int kDmaPerStage = 2 * (kBK / 16);     // DMA instructions per wave per stage (A and B)
+static_assert(kKPad % kBK == 0, "k padding must cover whole K steps");
+static_assert(kDmaPerStage == 8, "the vmcnt immediates below assume 8 DMA instructions per stage");
 
 __device__ __forceinline__ v4i as_v4i(const uint4& v) { return v4i{int(v.x), int(v.y), int(v.z), int(v.w)}; }
 
@@ -50,6 +58,14 @@ __device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int& ti, int&
     tj = panel * GW + in_panel % w;
 }
 
+// 64 lanes x 16 B from global memory into LDS: lane l's 16 bytes land at lds_addr + 16*l.
+// The LDS byte address travels in M0.  The compiler does not see this as a memory access, so
+// completion is awaited with explicit s_waitcnt vmcnt(...) below.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(gptr) : "memory");
+}
+
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__ As,
                                                       const int8_t* __restrict__ Bs,
                                                       int32_t* __restrict__ P, int64_t mp,
@@ -66,7 +82,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), ti, tj);
     const int64_t i0 = int64_t(ti) * kBM, j0 = int64_t(tj) * kBN;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wi = wave & 1, wj = wave >> 1;
 
     v16i acc[4][4];   // [fj][fi]
@@ -82,111 +99,115 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
         return int((k1 - k0) / kBK);
     };
 
-    // (nkb_, nd, ns, nkt) walks the (k-block, anti-diagonal, pair, K step) sequence one tile
-    // ahead of the compute, so the prefetch runs across pair and anti-diagonal boundaries
-    // without a bubble.  After the last tile it stays put (the final prefetch is discarded).
+    // (nkb_, nd, ns, nkt) walks the (k-block, anti-diagonal, pair, K step) sequence ahead of the
+    // compute, so the prefetch runs across pair and anti-diagonal boundaries without a bubble.
+    // After the last tile it stays put: the surplus transfers land in stages nobody reads again.
     int nkb_ = 0, nd = 0, ns = 0, nkt = 0;
     int nxt_ktc = kt_count(0);
-    const uint4* gA = reinterpret_cast<const uint4*>(As) + i0 + threadIdx.x;
-    const uint4* gB = reinterpret_cast<const uint4*>(Bs) + j0 + threadIdx.x;
-    const int64_t planeA = (kp / 16) * mp, planeB = (kp / 16) * np;   // uint4 per slice plane
+    int issue_stage = 0;
+    const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) uint8_t*)lds));
+    const uint8_t* gA = reinterpret_cast<const uint8_t*>(As) + (i0 + threadIdx.x) * 16;
+    const uint8_t* gB = reinterpret_cast<const uint8_t*>(Bs) + (j0 + threadIdx.x) * 16;
+    const int64_t planeA = kp * mp, planeB = kp * np;   // bytes per slice plane
 
-    // The prefetch is issued with inline assembly: a plain C++ load from read-only memory is moved
-    // by the compiler down to its use (the LDS store after the MFMA block), which would expose the
-    // whole memory latency.  The compiler does not count these loads, so OZ_WAIT_PREFETCH() waits
-    // for them explicitly and ties the staging registers to the wait.
-    v4i sa[kBK / 16], sb[kBK / 16];
-#define OZ_PREFETCH()                                                                        \
-    {                                                                                        \
-        const int64_t kc = (int64_t(nkb_) * kblk) / 16 + int64_t(nkt) * (kBK / 16);          \
-        const uint4* pa = gA + int64_t(ns) * planeA + kc * mp;                               \
-        const uint4* pb = gB + int64_t(nd - ns) * planeB + kc * np;                          \
-        _Pragma("unroll") for (int q = 0; q < kBK / 16; ++q) {                               \
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sa[q]) : "v"(pa + q * mp)); \
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sb[q]) : "v"(pb + q * np)); \
-        }                                                                                    \
+    // addresses of the next tile to fetch (8 transfers per wave: 4 k chunks of A, 4 of B)
+    const uint8_t* pa;
+    const uint8_t* pb;
+    uint32_t la;
+#define OZ_TILE_ADDR()                                                                           \
+    {                                                                                            \
+        const int64_t kc = (int64_t(nkb_) * kblk) / 16 + int64_t(nkt) * (kBK / 16);              \
+        pa = gA + int64_t(ns) * planeA + kc * mp * 16;                                           \
+        pb = gB + int64_t(nd - ns) * planeB + kc * np * 16;                                      \
+        la = lds_base + issue_stage * kStageBytes + wave * 1024;                                 \
     }
-#define OZ_ADVANCE()                                                                         \
-    {                                                                                        \
-        if (++nkt == nxt_ktc) {                                                              \
-            nkt = 0;                                                                         \
-            if (++ns > nd) {                                                                 \
-                ns = 0;                                                                      \
-                if (++nd == S) {                                                             \
-                    nd = 0;                                                                  \
-                    if (++nkb_ == nkb) nkb_ = nkb - 1;                                       \
-                    nxt_ktc = kt_count(nkb_);                                                \
-                }                                                                            \
-            }                                                                                \
-        }                                                                                    \
+// transfer number x (0..7) of the tile addressed by OZ_TILE_ADDR
+#define OZ_DMA(x)                                                                                \
+    {                                                                                            \
+        if ((x) & 1) dma16(pb + ((x) >> 1) * np * 16, la + kBM * kBK + ((x) >> 1) * (kBN * 16)); \
+        else dma16(pa + ((x) >> 1) * mp * 16, la + ((x) >> 1) * (kBM * 16));                     \
     }
-#define OZ_WAIT_PREFETCH()                                                                   \
-    asm volatile("s_waitcnt vmcnt(0)"                                                        \
-                 : "+v"(sa[0]), "+v"(sa[1]), "+v"(sa[2]), "+v"(sa[3]), "+v"(sa[4]), "+v"(sa[5]), \
-                   "+v"(sa[6]), "+v"(sa[7]), "+v"(sb[0]), "+v"(sb[1]), "+v"(sb[2]), "+v"(sb[3]), \
-                   "+v"(sb[4]), "+v"(sb[5]), "+v"(sb[6]), "+v"(sb[7]))
-#define OZ_STAGE_TO_LDS(stage)                                                               \
-    {                                                                                        \
-        v4i* wa = reinterpret_cast<v4i*>(lds + (stage) * kStageBytes) + threadIdx.x;         \
-        v4i* wb = reinterpret_cast<v4i*>(lds + (stage) * kStageBytes + kBM * kBK) + threadIdx.x; \
-        _Pragma("unroll") for (int q = 0; q < kBK / 16; ++q) {                               \
-            wa[q * kBM] = sa[q];                                                             \
-            wb[q * kBN] = sb[q];                                                             \
-        }                                                                                    \
+#define OZ_TILE_ADVANCE()                                                                        \
+    {                                                                                            \
+        issue_stage = (issue_stage + 1) & (kStages - 1);                                         \
+        if (++nkt == nxt_ktc) {                                                                  \
+            nkt = 0;                                                                             \
+            if (++ns > nd) {                                                                     \
+                ns = 0;                                                                          \
+                if (++nd == S) {                                                                 \
+                    nd = 0;                                                                      \
+                    if (++nkb_ == nkb) nkb_ = nkb - 1;                                           \
+                    nxt_ktc = kt_count(nkb_);                                                    \
+                }                                                                                \
+            }                                                                                    \
+        }                                                                                        \
     }
+#define OZ_ISSUE_TILE()                                                                          \
+    {                                                                                            \
+        OZ_TILE_ADDR();                                                                          \
+        _Pragma("unroll") for (int x = 0; x < 8; ++x) OZ_DMA(x);                                 \
+        OZ_TILE_ADVANCE();                                                                       \
+    }
+// operand fragment f of K sub-step kk (0 or 1) of the tile in LDS stage `stage`
+#define OZ_READ_A(dst, stage, kk, f)                                                             \
+    dst[f] = as_v4i((reinterpret_cast<const uint4*>(lds + (stage) * kStageBytes) + wi * 128 +    \
+                     (lane & 31) + ((kk) * 2 + (lane >> 5)) * kBM)[(f) * 32])
+#define OZ_READ_B(dst, stage, kk, f)                                                             \
+    dst[f] = as_v4i((reinterpret_cast<const uint4*>(lds + (stage) * kStageBytes + kBM * kBK) +   \
+                     wj * 128 + (lane & 31) + ((kk) * 2 + (lane >> 5)) * kBN)[(f) * 32])
+#define OZ_READ_FRAGS(dstA, dstB, stage, kk)                                                     \
+    _Pragma("unroll") for (int f = 0; f < 4; ++f) {                                              \
+        OZ_READ_A(dstA, stage, kk, f);                                                           \
+        OZ_READ_B(dstB, stage, kk, f);                                                           \
+    }
+#define OZ_MFMA(srcA, srcB, fj, fi)                                                              \
+    acc[fj][fi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(srcB[fj], srcA[fi], acc[fj][fi], 0, 0, 0)
 
-    static_assert(kBK / 16 == 8, "OZ_WAIT_PREFETCH lists 8 + 8 staging registers");
-    OZ_PREFETCH();
-    OZ_ADVANCE();
-    OZ_WAIT_PREFETCH();
-    OZ_STAGE_TO_LDS(0);
-    __syncthreads();
+    // prologue: three tiles in flight, then wait for the first, publish it, issue the fourth
+    OZ_ISSUE_TILE();
+    OZ_ISSUE_TILE();
+    OZ_ISSUE_TILE();
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+    OZ_ISSUE_TILE();
+    v4i fa0[4], fb0[4], fa1[4], fb1[4];
+    int stage = 0;
+    OZ_READ_FRAGS(fa0, fb0, stage, 0);
 
-    int buf = 0;
     for (int kb = 0; kb < nkb; ++kb) {
         const int ktc = kt_count(kb);
         for (int d = 0; d < S; ++d) {
             const int n_iter = (d + 1) * ktc;
             for (int it = 0; it < n_iter; ++it) {
-                OZ_PREFETCH();
-                __builtin_amdgcn_sched_barrier(0);
-
-                const uint4* la = reinterpret_cast<const uint4*>(lds + buf * kStageBytes) + wi * 128 +
-                                  (lane & 31) + (lane >> 5) * kBM;
-                const uint4* lb = reinterpret_cast<const uint4*>(lds + buf * kStageBytes + kBM * kBK) +
-                                  wj * 128 + (lane & 31) + (lane >> 5) * kBN;
-                // operand fragments are double buffered in registers: the LDS reads of K sub-step
-                // kk+1 are issued before the 16 MFMAs of sub-step kk
-                v4i fa[2][4], fb[2][4];
+                // invariant here: transfers of the next three tiles are in flight (24 per wave);
+                // fragments of sub-step 0 of the current tile are in fa0/fb0
+                // first half: MFMAs of sub-step 0; the LDS reads of sub-step 1 ride along
 #pragma unroll
-                for (int f = 0; f < 4; ++f) {
-                    fa[0][f] = as_v4i(la[f * 32]);
-                    fb[0][f] = as_v4i(lb[f * 32]);
-                }
-#pragma unroll
-                for (int kk = 0; kk < kBK / 32; ++kk) {
-                    if (kk + 1 < kBK / 32) {
-#pragma unroll
-                        for (int f = 0; f < 4; ++f) {
-                            fa[(kk + 1) & 1][f] = as_v4i(la[(kk + 1) * 2 * kBM + f * 32]);
-                            fb[(kk + 1) & 1][f] = as_v4i(lb[(kk + 1) * 2 * kBN + f * 32]);
-                        }
-                    }
-#pragma unroll
-                    for (int fj = 0; fj < 4; ++fj)
-#pragma unroll
-                        for (int fi = 0; fi < 4; ++fi)
-                            acc[fj][fi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                                fb[kk & 1][fj], fa[kk & 1][fi], acc[fj][fi], 0, 0, 0);
+                for (int g = 0; g < 8; ++g) {
+                    if (g < 4) { OZ_READ_A(fa1, stage, 1, g); OZ_READ_B(fb1, stage, 1, g); }
+                    __builtin_amdgcn_sched_barrier(0);
+                    OZ_MFMA(fa0, fb0, g >> 1, (g & 1) * 2);
+                    OZ_MFMA(fa0, fb0, g >> 1, (g & 1) * 2 + 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-
-                // unconditional: after the last tile this rewrites a stage nobody reads again
-                OZ_WAIT_PREFETCH();
-                OZ_STAGE_TO_LDS(buf ^ 1);
-                OZ_ADVANCE();
-                __syncthreads();
-                buf ^= 1;
+                // next tile landed (own transfers), every LDS read of this tile returned; after the
+                // barrier that holds for all waves, so this stage may be overwritten
+                asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                const int next_stage = (stage + 1) & (kStages - 1);
+                OZ_TILE_ADDR();
+                // second half: MFMAs of sub-step 1; one transfer of the tile three stages ahead is
+                // issued per MFMA pair, so a full memory queue delays at most one pair; the LDS
+                // reads of the next tile's sub-step 0 ride along
+#pragma unroll
+                for (int g = 0; g < 8; ++g) {
+                    if (g < 4) { OZ_READ_A(fa0, next_stage, 0, g); OZ_READ_B(fb0, next_stage, 0, g); }
+                    __builtin_amdgcn_sched_barrier(0);
+                    OZ_MFMA(fa1, fb1, g >> 1, (g & 1) * 2);
+                    OZ_MFMA(fa1, fb1, g >> 1, (g & 1) * 2 + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    OZ_DMA(g);
+                }
+                OZ_TILE_ADVANCE();
+                stage = next_stage;
             }
 
             // anti-diagonal d of k-block kb is complete: write the tile and restart from zero.
@@ -207,12 +228,18 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                 }
         }
     }
+    // drain the surplus transfers before the workgroup's LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-#undef OZ_PREFETCH
-#undef OZ_ADVANCE
-#undef OZ_WAIT_PREFETCH
-#undef OZ_STAGE_TO_LDS
+#undef OZ_ISSUE_TILE
+#undef OZ_READ_FRAGS
+#undef OZ_MFMA
+#undef OZ_DMA
+#undef OZ_TILE_ADDR
+#undef OZ_TILE_ADVANCE
+#undef OZ_READ_A
+#undef OZ_READ_B
 
 void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p) {
     static bool attr_set = false;
