@@ -61,9 +61,11 @@ __device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int& ti, int&
 // 64 lanes x 16 B from global memory into LDS: lane l's 16 bytes land at lds_addr + 16*l.
 // The LDS byte address travels in M0.  The compiler does not see this as a memory access, so
 // completion is awaited with explicit s_waitcnt vmcnt(...) below.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_addr), "v"(gptr) : "memory");
+// The global address is a wave-uniform base (scalar registers) plus a per-lane byte offset, so
+// stepping through the tiles costs scalar arithmetic only.
+__device__ __forceinline__ void dma16(const uint8_t* gbase, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(gbase) : "memory");
 }
 
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__ As,
@@ -106,8 +108,9 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     int nxt_ktc = kt_count(0);
     int issue_stage = 0;
     const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) uint8_t*)lds));
-    const uint8_t* gA = reinterpret_cast<const uint8_t*>(As) + (i0 + threadIdx.x) * 16;
-    const uint8_t* gB = reinterpret_cast<const uint8_t*>(Bs) + (j0 + threadIdx.x) * 16;
+    const uint8_t* gA = reinterpret_cast<const uint8_t*>(As) + (i0 + wave * 64) * 16;   // wave-uniform
+    const uint8_t* gB = reinterpret_cast<const uint8_t*>(Bs) + (j0 + wave * 64) * 16;
+    const uint32_t lane_off = uint32_t(lane) * 16;
     const int64_t planeA = kp * mp, planeB = kp * np;   // bytes per slice plane
 
     // addresses of the next tile to fetch (8 transfers per wave: 4 k chunks of A, 4 of B)
@@ -124,8 +127,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 // transfer number x (0..7) of the tile addressed by OZ_TILE_ADDR
 #define OZ_DMA(x)                                                                                \
     {                                                                                            \
-        if ((x) & 1) dma16(pb + ((x) >> 1) * np * 16, la + kBM * kBK + ((x) >> 1) * (kBN * 16)); \
-        else dma16(pa + ((x) >> 1) * mp * 16, la + ((x) >> 1) * (kBM * 16));                     \
+        if ((x) & 1) dma16(pb + ((x) >> 1) * np * 16, lane_off, la + kBM * kBK + ((x) >> 1) * (kBN * 16)); \
+        else dma16(pa + ((x) >> 1) * mp * 16, lane_off, la + ((x) >> 1) * (kBM * 16));           \
     }
 #define OZ_TILE_ADVANCE()                                                                        \
     {                                                                                            \
