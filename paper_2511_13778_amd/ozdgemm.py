@@ -225,6 +225,28 @@ class Gemm:
             out.append(t.cpu().numpy())
         return out
 
+    def slices_sampled(self, S, rows, cols):
+        """(As[:, rows, :], Bs[:, cols, :]) as numpy int8 arrays; the selection happens on the device."""
+        import torch
+        L = self.L
+        out = []
+        for off, rows_p, sel in ((L.off_As, L.mp, rows), (L.off_Bs, L.np, cols)):
+            t = self._view(off, L.s_cap * L.kp * rows_p, torch.int8).view(L.s_cap, L.kp // 16, rows_p, 16)
+            idx = torch.as_tensor(sel, device="cuda", dtype=torch.long)
+            t = t[:S].index_select(2, idx).permute(0, 2, 1, 3).reshape(S, len(sel), L.kp)[:, :, :self.k]
+            out.append(t.cpu().numpy())
+        return out
+
+    def products_sampled(self, S, nkb, rows, cols):
+        """P[:, :, rows, cols] as a numpy int32 array nkb x S x len(rows) x len(cols)."""
+        import torch
+        L = self.L
+        t = self._view(L.off_P, L.nkb * L.s_cap * L.np * L.mp * 4, torch.int32).view(L.nkb, L.s_cap, L.np, L.mp)
+        ri = torch.as_tensor(rows, device="cuda", dtype=torch.long)
+        ci = torch.as_tensor(cols, device="cuda", dtype=torch.long)
+        t = t[:nkb, :S].index_select(2, ci).index_select(3, ri)
+        return t.permute(0, 1, 3, 2).cpu().numpy()
+
     def products(self, S, nkb):
         """P as numpy int32 nkb x S x m x n."""
         import torch
