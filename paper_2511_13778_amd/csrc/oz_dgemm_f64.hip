@@ -30,9 +30,19 @@ __device__ __forceinline__ void dg_load(double (&v)[8], const double* __restrict
         if (ROWS_CONTIG) { rr = threadIdx.x & 127; ll = (threadIdx.x >> 7) + 2 * q; }
         else { ll = threadIdx.x & 15; rr = (threadIdx.x >> 4) + 16 * q; }
         const int64_t r = r0 + rr, l = l0 + ll;
-        v[q] = (r < rows && l < k) ? X[r * stride_r + l * stride_l] : 0.0;
+        // clamped address + select: the load is unconditional, so the loop stays branch-free
+        const int64_t rc = r < rows ? r : rows - 1, lc = l < k ? l : k - 1;
+        const double x = X[rc * stride_r + lc * stride_l];
+        v[q] = (r < rows && l < k) ? x : 0.0;
     }
 }
+// interior tiles (no bounds to check): p points at this thread's first element of the K step,
+// the other seven are q*qstep elements further on
+__device__ __forceinline__ void dg_load_interior(double (&v)[8], const double* __restrict__ p, int64_t qstep) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = p[q * qstep];
+}
+
 template <bool ROWS_CONTIG>
 __device__ __forceinline__ void dg_store(const double (&v)[8], double* lds) {
 #pragma unroll
@@ -44,7 +54,7 @@ __device__ __forceinline__ void dg_store(const double (&v)[8], double* lds) {
     }
 }
 
-template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG>
+template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, bool EDGE>
 __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     const Record* rec, int64_t m, int64_t n, int64_t k, double alpha, const double* __restrict__ A,
     int64_t a_sr, int64_t a_sl, const double* __restrict__ B, int64_t b_sr, int64_t b_sl, double beta,
@@ -64,8 +74,19 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         for (int b = 0; b < 4; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
 
     double va[8], vb[8];
-    dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, 0, k);
-    dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, 0, k);
+    // EDGE == false: m, n multiples of the tile and k a multiple of the K step
+    const double* pa = A + (A_ROWS_CONTIG ? (i0 + (threadIdx.x & 127)) * a_sr + (threadIdx.x >> 7) * a_sl
+                                          : (i0 + (threadIdx.x >> 4)) * a_sr + (threadIdx.x & 15) * a_sl);
+    const double* pb = B + (B_ROWS_CONTIG ? (j0 + (threadIdx.x & 127)) * b_sr + (threadIdx.x >> 7) * b_sl
+                                          : (j0 + (threadIdx.x >> 4)) * b_sr + (threadIdx.x & 15) * b_sl);
+    const int64_t qa = A_ROWS_CONTIG ? 2 * a_sl : 16 * a_sr, qb = B_ROWS_CONTIG ? 2 * b_sl : 16 * b_sr;
+    if (EDGE) {
+        dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, 0, k);
+        dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, 0, k);
+    } else {
+        dg_load_interior(va, pa, qa);
+        dg_load_interior(vb, pb, qb);
+    }
     dg_store<A_ROWS_CONTIG>(va, At[0]);
     dg_store<B_ROWS_CONTIG>(vb, Bt[0]);
     __syncthreads();
@@ -74,8 +95,15 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     for (int64_t l0 = 0; l0 < k; l0 += kDK) {
         const bool have_next = l0 + kDK < k;
         if (have_next) {
-            dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
-            dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
+            if (EDGE) {
+                dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
+                dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
+            } else {
+                pa += kDK * a_sl;
+                pb += kDK * b_sl;
+                dg_load_interior(va, pa, qa);
+                dg_load_interior(vb, pb, qb);
+            }
         }
         const double* la = At[buf] + wi * 64 + (lane & 15);
         const double* lb = Bt[buf] + wj * 64 + (lane & 15);
@@ -108,7 +136,7 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
             for (int r = 0; r < 4; ++r) {
                 const int64_t j = j0 + wj * 64 + fj * 16 + 4 * r + (lane >> 4);
                 const int64_t i = i0 + wi * 64 + fi * 16 + (lane & 15);
-                if (i < m && j < n) {
+                if (!EDGE || (i < m && j < n)) {
                     double out = __dmul_rn(alpha, acc[fj][fi][r]);
                     if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
                     C[j * ldc + i] = out;
@@ -126,12 +154,18 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
     const int ntm = int((m + kDM - 1) / kDM), ntn = int((n + kDN - 1) / kDN);
     const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
     const bool ac = !ta, bc = tb;
-#define OZ_DG(AC, BC) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC>), grid, block, 0, st, rec, m, n, k, alpha, A, \
-                                         a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm)
-    if (ac && bc) OZ_DG(true, true);
-    else if (ac && !bc) OZ_DG(true, false);
-    else if (!ac && bc) OZ_DG(false, true);
-    else OZ_DG(false, false);
+    const bool edge = (m % kDM) || (n % kDN) || (k % kDK);
+#define OZ_DG(AC, BC)                                                                                          \
+    {                                                                                                          \
+        if (edge) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, true>), grid, block, 0, st, rec, m, n, k, alpha, A, \
+                                     a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm);                            \
+        else hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, false>), grid, block, 0, st, rec, m, n, k, alpha, A, \
+                                a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm);                                 \
+    }
+    if (ac && bc) OZ_DG(true, true)
+    else if (ac && !bc) OZ_DG(true, false)
+    else if (!ac && bc) OZ_DG(false, true)
+    else OZ_DG(false, false)
 #undef OZ_DG
 }
 

@@ -295,12 +295,13 @@ def test_heuristic_sends_small_problems_native(lib):
     assert np.allclose(got, A @ B, rtol=0, atol=48 * 2.0 ** -53 * 48)
 
 
+@pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512)])   # ragged path, interior fast path
 @pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
-def test_native_fp64_gemm(lib, ta, tb):
+def test_native_fp64_gemm(lib, ta, tb, shape):
     g, h = lib
-    m, n, k = 200, 150, 333
+    m, n, k = shape
     A, B, Cin = wl.lognormal_spread(m, k, n, 0.5, seed=40, with_c=True)
-    got, _, res = run_gpu(g, h, A, B, 1.5, 0.5, Cin, ta, tb, pad=2, mode=g.OZ_NATIVE)
+    got, _, res = run_gpu(g, h, A, B, 1.5, 0.5, Cin, ta, tb, pad=2 if m % 128 else 0, mode=g.OZ_NATIVE)
     assert (res.fallback, res.reason) == (1, oz.REASON_NATIVE)
     idx = [(i, j) for i in range(0, m, 13) for j in range(0, n, 11)]
     exact = ex.exact_entries(A, B, idx, 1.5, 0.5, Cin)
