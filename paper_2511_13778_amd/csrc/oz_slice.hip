@@ -70,6 +70,48 @@ __device__ __forceinline__ void emit_slices(const Fixed (&f)[16], int S, int8_t*
     }
 }
 
+// Up to 8 slices the whole fixed-point value fits one 64-bit word, and the carry chain of the remap
+// collapses into one addition: with BIAS = 0x80 in every sub-leading byte, the digits are the bytes
+// of X + BIAS with the top bit of every sub-leading byte flipped.  Byte b of 16 values is gathered
+// into four dwords with byte permutes (three per dword).
+__device__ __forceinline__ void emit_slices_64(const Fixed (&f)[16], int S, int8_t* dst, int64_t slice_stride) {
+    const uint64_t bias = S >= 2 ? (0x8080808080808080ull >> (8 * (9 - S))) : 0ull;
+    uint32_t lo[16], hi[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const uint64_t y = (uint64_t(f[e].W) << min(f[e].o, 63)) + bias;
+        lo[e] = uint32_t(y);
+        hi[e] = uint32_t(y >> 32);
+    }
+    for (int b = S - 1; b >= 0; --b) {
+        const uint32_t k = uint32_t(b) & 3u;
+        const uint32_t pick = k * 0x0101u + 0x0400u;            // result bytes: [second.k, first.k, -, -]
+        const uint32_t flip = (b == S - 1) ? 0u : 0x80808080u;  // the leading digit keeps its sign bit
+        uint32_t w[4];
+        if (b >= 4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t t1 = __builtin_amdgcn_perm(hi[4 * j + 1], hi[4 * j], pick);
+                const uint32_t t2 = __builtin_amdgcn_perm(hi[4 * j + 3], hi[4 * j + 2], pick);
+                w[j] = __builtin_amdgcn_perm(t2, t1, 0x05040100u) ^ flip;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t t1 = __builtin_amdgcn_perm(lo[4 * j + 1], lo[4 * j], pick);
+                const uint32_t t2 = __builtin_amdgcn_perm(lo[4 * j + 3], lo[4 * j + 2], pick);
+                w[j] = __builtin_amdgcn_perm(t2, t1, 0x05040100u) ^ flip;
+            }
+        }
+        *reinterpret_cast<uint4*>(dst + int64_t(S - 1 - b) * slice_stride) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+__device__ __forceinline__ void emit(const Fixed (&f)[16], int S, int8_t* dst, int64_t slice_stride) {
+    if (S <= 8) emit_slices_64(f, S, dst, slice_stride);
+    else emit_slices(f, S, dst, slice_stride);
+}
+
 constexpr int kSliceChunksPerWg = 4;
 
 // Rows contiguous in memory: thread = row, lanes along rows; loads coalesce across the wave.
@@ -92,7 +134,7 @@ __global__ __launch_bounds__(256) void slice_rows_contig_kernel(
             const uint64_t bits = (r < rows && l < k) ? src[l * stride_l] : 0ull;
             f[e] = fixed_point(bits, er, S);
         }
-        emit_slices(f, S, out + (c * rows_p + r) * 16, slice_stride);
+        emit(f, S, out + (c * rows_p + r) * 16, slice_stride);
     }
 }
 
@@ -125,7 +167,7 @@ __global__ __launch_bounds__(256) void slice_k_contig_kernel(
 #pragma unroll
     for (int e = 0; e < 16; ++e) f[e] = fixed_point(T[rr][cc * 16 + e], er, S);
     const int64_t c = l0 / 16 + cc;
-    emit_slices(f, S, out + (c * rows_p + r) * 16, kp * rows_p);
+    emit(f, S, out + (c * rows_p + r) * 16, kp * rows_p);
 }
 
 void launch_slice(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l, int64_t rows,
