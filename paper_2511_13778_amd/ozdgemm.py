@@ -56,6 +56,12 @@ def load_library() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("%s is missing: build it with `python -m paper_2511_13778_amd.build` "
                            "(there is no CPU fallback)" % LIB_PATH)
+    try:
+        # torch ships its own HIP runtime; loading it first makes this library bind to the same copy
+        # (two runtimes in one process do not both see the GPU)
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     H = C.c_void_p
     lib.oz_create.argtypes = [C.POINTER(H), C.c_int]
