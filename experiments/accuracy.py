@@ -3,8 +3,8 @@
 
   test2   generalised BLAS-grading Test 2 (aspect A1): n = 1024, exponent-range parameter b swept,
           several mantissa-bit settings, without guardrails (FIXED_UNGUARDED) and with guardrails
-          and automatic fallback (FIXED_GUARDED with target_bits = max_bits - 2, i.e. the guard trips
-          when the ESC exceeds 2).  Error measure as in the paper: diagonal entries
+          and automatic fallback (FIXED_GUARDED with target_bits = 53: the guard trips when
+          53 + ESC exceeds the configured bits, so settings below 54 bits always fall back).  Error measure as in the paper: diagonal entries
           against x^T x accumulated in extended precision (FP80), off-diagonal entries against a
           reference O(n^3) floating-point product.
   gradeA  maximum and average componentwise relative error |fl(AB) - AB| / (|A||B|) against n for
@@ -62,7 +62,7 @@ def test2(g, h, nn, bits_list, b_list, seed, lines):
         row, esc = [], None
         for mb in bits_list:
             Cu, _ = run(g, h, A, B, mode=g.OZ_FIXED_UNGUARDED, max_bits=mb, heuristic=0)
-            Cg, rg = run(g, h, A, B, mode=g.OZ_FIXED_GUARDED, target_bits=max(1, mb - 2), max_bits=mb, heuristic=0)
+            Cg, rg = run(g, h, A, B, mode=g.OZ_FIXED_GUARDED, target_bits=53, max_bits=mb, heuristic=0)
             esc = rg.esc
             row.append("%18.3e  %8.2e%s" % (err(Cu), err(Cg), "F" if rg.fallback else " "))
         lines.append("%-4d %-4d " % (b, esc) + "  ".join(row))
