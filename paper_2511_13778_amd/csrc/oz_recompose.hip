@@ -14,7 +14,7 @@
 
 namespace oz {
 
-constexpr int kRecElemsPerThread = 4;
+constexpr int kRecElemsPerThread = 4;   // four consecutive i per thread: one 16-byte load per plane
 
 __global__ __launch_bounds__(256) void recompose_kernel(const int32_t* __restrict__ P,
                                                         const int32_t* __restrict__ eA,
@@ -28,23 +28,32 @@ __global__ __launch_bounds__(256) void recompose_kernel(const int32_t* __restric
     const int64_t kblk = ((int64_t(1) << 17) - 1) / S / 256 * 256;
     const int nkb = int((kp + kblk - 1) / kblk);
     const int64_t j = blockIdx.y;
+    const int64_t i0 = (int64_t(blockIdx.x) * 256 + threadIdx.x) * kRecElemsPerThread;
+    if (i0 >= m) return;
     const int eb = eB[j];
     const int64_t plane = np * mp;
-#pragma unroll
-    for (int q = 0; q < kRecElemsPerThread; ++q) {
-        const int64_t i = (int64_t(blockIdx.x) * kRecElemsPerThread + q) * 256 + threadIdx.x;
-        if (i >= m) continue;
-        const int32_t* p = P + j * mp + i;
-        double R = 0.0;
-        for (int kb = 0; kb < nkb; ++kb) {
-            double Rb = 0.0;
-            for (int d = S - 1; d >= 0; --d)
-                Rb = double(p[(int64_t(kb) * s_cap + d) * plane]) + Rb * 0x1p-8;
-            R = R + Rb;
+    const int4* p = reinterpret_cast<const int4*>(P + j * mp + i0);   // mp and i0 are multiples of 4
+    double R[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int kb = 0; kb < nkb; ++kb) {
+        double Rb[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int d = S - 1; d >= 0; --d) {
+            const int4 v = p[((int64_t(kb) * s_cap + d) * plane) / 4];
+            Rb[0] = double(v.x) + Rb[0] * 0x1p-8;
+            Rb[1] = double(v.y) + Rb[1] * 0x1p-8;
+            Rb[2] = double(v.z) + Rb[2] * 0x1p-8;
+            Rb[3] = double(v.w) + Rb[3] * 0x1p-8;
         }
-        const int ea = eA[i];
-        const int sc = (ea > kExpAllZero ? ea : 0) + (eb > kExpAllZero ? eb : 0) + (2 * kHeadroomBits - 12);
-        const double ab = ldexp(R, sc);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) R[q] = R[q] + Rb[q];
+    }
+    const int4 ea4 = *reinterpret_cast<const int4*>(eA + i0);
+    const int ea[4] = {ea4.x, ea4.y, ea4.z, ea4.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t i = i0 + q;
+        if (i >= m) break;
+        const int sc = (ea[q] > kExpAllZero ? ea[q] : 0) + (eb > kExpAllZero ? eb : 0) + (2 * kHeadroomBits - 12);
+        const double ab = ldexp(R[q], sc);
         double out = __dmul_rn(alpha, ab);
         if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
         C[j * ldc + i] = out;

@@ -1,5 +1,6 @@
 // Pre-pass over op(A) and op(B): Inf/NaN scan, per-block exponent Max/Min tables for the
-// coarsened ESC, and the row / column exponents the slicing aligns to.
+// coarsened ESC, and the row / column exponents the slicing aligns to (integer atomicMax over the
+// block maxima: order-free, hence deterministic).
 // (paper: sections "Pre-processing and Safety Checks" and "Exponent Span Estimation";
 //  block Max/Min: section "ESC", the paragraph on blocks of length b.)
 //
@@ -37,11 +38,15 @@ struct BlockStat {
     }
 };
 
-__global__ void init_kernel(Record* rec) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
+// resets the control record and the row / column exponents (targets of atomicMax in the scans)
+__global__ __launch_bounds__(256) void init_kernel(Record* rec, int32_t* eA, int64_t mp, int32_t* eB, int64_t np) {
+    const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (t == 0) {
         rec->infnan = 0;
         rec->span_max = 0;
     }
+    if (t < mp) eA[t] = kExpAllZero;
+    if (t < np) eB[t] = kExpAllZero;
 }
 
 // Rows contiguous in memory (stride_r == 1): one thread per row, lanes along the rows, so
@@ -51,10 +56,12 @@ constexpr int kScanBlocksPerWg = 4;
 
 __global__ __launch_bounds__(256) void scan_rows_contig_kernel(
     const double* __restrict__ X, int64_t stride_l, int64_t rows, int64_t rows_p, int64_t k,
-    int b, int G, int16_t* __restrict__ tab, int max_half, Record* rec, int check) {
+    int b, int G, int16_t* __restrict__ tab, int max_half, int32_t* __restrict__ e_out, Record* rec,
+    int check) {
     const int64_t r = int64_t(blockIdx.x) * 256 + threadIdx.x;
     const int g0 = blockIdx.y * kScanBlocksPerWg;
     int bad = 0;
+    int row_max = kExpAllZero;
     for (int g = g0; g < min(G, g0 + kScanBlocksPerWg); ++g) {
         BlockStat st;
         st.reset();
@@ -67,7 +74,9 @@ __global__ __launch_bounds__(256) void scan_rows_contig_kernel(
         }
         tab[(int64_t(max_half ? g : G + g)) * rows_p + r] = st.table_max();
         tab[(int64_t(max_half ? G + g : g)) * rows_p + r] = st.table_min();
+        row_max = max(row_max, int(st.table_max()));
     }
+    if (row_max > kExpAllZero) atomicMax(&e_out[r], row_max);
     if (check && bad) atomicOr(&rec->infnan, 1);
 }
 
@@ -76,7 +85,9 @@ __global__ __launch_bounds__(256) void scan_rows_contig_kernel(
 // A workgroup covers 16 rows; grid: (rows_p/16, ceil(G/kBlocksPerWg)).
 __global__ __launch_bounds__(256) void scan_k_contig_kernel(
     const double* __restrict__ X, int64_t stride_r, int64_t rows, int64_t rows_p, int64_t k,
-    int b, int G, int16_t* __restrict__ tab, int max_half, Record* rec, int check) {
+    int b, int G, int16_t* __restrict__ tab, int max_half, int32_t* __restrict__ e_out, Record* rec,
+    int check) {
+    int row_max = kExpAllZero;
     const int q = threadIdx.x & 15;
     const int64_t r = int64_t(blockIdx.x) * 16 + (threadIdx.x >> 4);
     const int g0 = blockIdx.y * kScanBlocksPerWg;
@@ -101,24 +112,16 @@ __global__ __launch_bounds__(256) void scan_k_contig_kernel(
         if (q == 0) {
             tab[(int64_t(max_half ? g : G + g)) * rows_p + r] = st.table_max();
             tab[(int64_t(max_half ? G + g : g)) * rows_p + r] = st.table_min();
+            row_max = max(row_max, int(st.table_max()));
         }
     }
+    if (q == 0 && row_max > kExpAllZero) atomicMax(&e_out[r], row_max);
     if (check && bad) atomicOr(&rec->infnan, 1);
 }
 
-// e[r] = max over blocks of the block maxima (kExpAllZero for an all-zero or padded row).
-__global__ __launch_bounds__(256) void row_exponent_kernel(const int16_t* __restrict__ tab_max,
-                                                           int G, int64_t rows_p,
-                                                           int32_t* __restrict__ e) {
-    const int64_t r = int64_t(blockIdx.x) * 256 + threadIdx.x;
-    if (r >= rows_p) return;
-    int mx = kExpAllZero;
-    for (int g = 0; g < G; ++g) mx = max(mx, int(tab_max[int64_t(g) * rows_p + r]));
-    e[r] = mx;
-}
-
-void launch_init(hipStream_t st, const Workspace& w, const Problem&) {
-    hipLaunchKernelGGL(init_kernel, dim3(1), dim3(64), 0, st, w.rec);
+void launch_init(hipStream_t st, const Workspace& w, const Problem& p) {
+    const int64_t nmax = p.mp > p.np ? p.mp : p.np;
+    hipLaunchKernelGGL(init_kernel, dim3(unsigned((nmax + 255) / 256)), dim3(256), 0, st, w.rec, w.eA, p.mp, w.eB, p.np);
 }
 
 void launch_scan(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l, int64_t rows,
@@ -127,16 +130,13 @@ void launch_scan(hipStream_t st, const double* X, int64_t stride_r, int64_t stri
     const int gy = (p.G + kScanBlocksPerWg - 1) / kScanBlocksPerWg;
     if (stride_r == 1) {
         hipLaunchKernelGGL(scan_rows_contig_kernel, dim3(unsigned(rows_p / 256), gy), dim3(256), 0, st,
-                           X, stride_l, rows, rows_p, p.k, p.esc_block, p.G, tab, int(max_first), rec,
+                           X, stride_l, rows, rows_p, p.k, p.esc_block, p.G, tab, int(max_first), e_out, rec,
                            int(check_infnan));
     } else {
         hipLaunchKernelGGL(scan_k_contig_kernel, dim3(unsigned(rows_p / 16), gy), dim3(256), 0, st, X,
-                           stride_r, rows, rows_p, p.k, p.esc_block, p.G, tab, int(max_first), rec,
+                           stride_r, rows, rows_p, p.k, p.esc_block, p.G, tab, int(max_first), e_out, rec,
                            int(check_infnan));
     }
-    const int16_t* tab_max = max_first ? tab : tab + int64_t(p.G) * rows_p;
-    hipLaunchKernelGGL(row_exponent_kernel, dim3(unsigned(rows_p / 256)), dim3(256), 0, st, tab_max,
-                       p.G, rows_p, e_out);
 }
 
 }  // namespace oz
