@@ -16,11 +16,14 @@ SOURCES = ["oz_api.hip", "oz_scan.hip", "oz_esc.hip", "oz_slice.hip", "oz_gemm_i
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+# per-source additions.  oz_esc.hip: MFMA results are consumed by the vector ALU right away, so they
+# are kept in ordinary VGPRs (the default puts them in accumulation registers and copies them out).
+SOURCE_FLAGS = {"oz_esc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str, extra=()) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *SOURCE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))

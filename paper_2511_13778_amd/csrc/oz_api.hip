@@ -80,6 +80,9 @@ bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, 
     return true;
 }
 
+// inner length of the BF16-encoded block tables: 2G rounded up to two MFMA K-steps of 16
+size_t enc_rows(const Problem& p) { return size_t((2 * p.G + 31) / 32) * 32; }
+
 void make_layout(const Problem& p, oz_layout_t& L) {
     size_t off = 0;
     L.mp = p.mp; L.np = p.np; L.kp = p.kp; L.s_cap = p.s_cap; L.nkb = p.nkb; L.kblk = p.kblk;
@@ -89,6 +92,8 @@ void make_layout(const Problem& p, oz_layout_t& L) {
     // block tables (not part of the published layout)
     off = align_up(off + size_t(2) * p.G * p.mp * 2);
     off = align_up(off + size_t(2) * p.G * p.np * 2);
+    off = align_up(off + enc_rows(p) * p.mp * 2);
+    off = align_up(off + enc_rows(p) * p.np * 2);
     L.off_As = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.mp);
     L.off_Bs = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.np);
     L.off_P = off; off = align_up(off + size_t(p.nkb) * p.s_cap * p.np * p.mp * 4);
@@ -103,8 +108,12 @@ Workspace bind(void* base, const Problem& p, const oz_layout_t& L) {
     w.eB = reinterpret_cast<int32_t*>(b + L.off_eB);
     size_t offU = align_up(L.off_eB + size_t(p.np) * 4);
     size_t offV = align_up(offU + size_t(2) * p.G * p.mp * 2);
+    size_t offEU = align_up(offV + size_t(2) * p.G * p.np * 2);
+    size_t offEV = align_up(offEU + enc_rows(p) * p.mp * 2);
     w.U = reinterpret_cast<int16_t*>(b + offU);
     w.V = reinterpret_cast<int16_t*>(b + offV);
+    w.EU = reinterpret_cast<uint16_t*>(b + offEU);
+    w.EV = reinterpret_cast<uint16_t*>(b + offEV);
     w.As = reinterpret_cast<int8_t*>(b + L.off_As);
     w.Bs = reinterpret_cast<int8_t*>(b + L.off_Bs);
     w.P = reinterpret_cast<int32_t*>(b + L.off_P);

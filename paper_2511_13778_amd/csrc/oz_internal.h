@@ -27,12 +27,13 @@ constexpr int kSumDeadBelow = -10000;
 // ---- tiling constants shared between kernels and the workspace layout --------------------
 constexpr int kRowPad = 256;          // rows of the slice panels are padded to this
 constexpr int kKPad = 128;            // k is padded to this (K tile of the INT8 GEMM)
-constexpr int kChunk = 16;            // bytes of k stored contiguously per row ("k chunk")
 
 // ---- device-resident control record ---------------------------------------------------
 struct Record {
     int32_t infnan;        // set by the scan kernels (atomicOr)
-    int32_t span_max;      // max_ij (eA_i + eB_j - zt_ij), set by the ESC kernel (atomicMax)
+    int32_t span_max;      // max_ij (eA_i + eB_j - zt_ij), set by the ESC kernels (atomicMax)
+    int32_t esc_exact;     // set by the MFMA ESC kernel when a pair needs the exact int16 kernel
+    int32_t pad_;
     oz_result_t res;       // written by the verdict kernel, read by every later kernel
 };
 
@@ -54,6 +55,8 @@ struct Workspace {
                            //           h >= G: Min exponent of block h-G
     int16_t* V;            // [2G][np]  h <  G: Min exponent of block h of column j of op(B)
                            //           h >= G: Max exponent of block h-G
+    uint16_t* EU;          // [ceil(2G/32)*4][mp][8] BF16 encoding of U relative to eA
+    uint16_t* EV;          // [ceil(2G/32)*4][np][8] BF16 encoding of V relative to eB
     int8_t* As;            // [s_cap][kp/16][mp][16]
     int8_t* Bs;            // [s_cap][kp/16][np][16]
     int32_t* P;            // [nkb][s_cap][np][mp]

@@ -44,6 +44,7 @@ __global__ __launch_bounds__(256) void init_kernel(Record* rec, int32_t* eA, int
     if (t == 0) {
         rec->infnan = 0;
         rec->span_max = 0;
+        rec->esc_exact = 0;
     }
     if (t < mp) eA[t] = kExpAllZero;
     if (t < np) eB[t] = kExpAllZero;

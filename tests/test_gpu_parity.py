@@ -206,6 +206,24 @@ def test_esc_block_lengths(lib, b):
     check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, esc_block=b, intermediates=False)
 
 
+@pytest.mark.parametrize("span", [30, 36, 37, 38, 39, 45, 70])
+def test_esc_across_matrix_unit_range(lib, span):
+    # One dot product whose best block candidate sits `span` bits below eA + eB: spans up to 37 are
+    # resolved by the matrix-unit ESC kernel, larger ones by the int16 kernel; both must be exact.
+    g, h = lib
+    rng = np.random.default_rng(span)
+    m, k, n = 70, 200, 150
+    A = rng.uniform(0.5, 1.0, (m, k)) * rng.choice([-1.0, 1.0], (m, k))
+    B = rng.uniform(0.5, 1.0, (k, n)) * rng.choice([-1.0, 1.0], (k, n))
+    i, j = 66, 131                                   # in the last 32x32 tile of each direction
+    A[i, 1:] *= 2.0 ** -span
+    B[0, j] *= 2.0 ** -span
+    B[2:, j] *= 2.0 ** -span
+    _, res, tr = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, bound=False,
+                                      intermediates=False)
+    assert res.esc == span + 1 and res.fallback == 0
+
+
 def test_grading_test2_guardrails(lib):
     g, h = lib
     A, B, x = wl.grading_test2(96, 40, seed=2)
