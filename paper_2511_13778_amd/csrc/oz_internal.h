@@ -34,6 +34,7 @@ struct Record {
     int32_t span_max;      // max_ij (eA_i + eB_j - zt_ij), set by the ESC kernels (atomicMax)
     int32_t esc_exact;     // set by the MFMA ESC kernel when a pair needs the exact int16 kernel
     int32_t pad_;
+    int32_t tile_sync[8];  // per-XCD arrival counters of the slice GEMM's workgroups
     oz_result_t res;       // written by the verdict kernel, read by every later kernel
 };
 

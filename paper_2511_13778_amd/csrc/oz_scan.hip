@@ -46,6 +46,9 @@ __global__ __launch_bounds__(256) void init_kernel(Record* rec, int32_t* eA, int
         rec->span_max = 0;
         rec->esc_exact = 0;
     }
+    if (t < 8) {
+        rec->tile_sync[t] = 0;
+    }
     if (t < mp) eA[t] = kExpAllZero;
     if (t < np) eB[t] = kExpAllZero;
 }
