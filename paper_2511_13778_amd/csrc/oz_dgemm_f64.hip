@@ -8,6 +8,10 @@
 // v_mfma_f64_16x16x4_f64; 128x128 tile per workgroup, 4 waves of 64x64 (4x4 MFMA tiles),
 // K step 16 through double-buffered LDS.  op(B) feeds the row operand and op(A) the column
 // operand so that the result's lane index runs along i and stores to column-major C coalesce.
+// LDS banks: a tile row (one k) is 130 doubles = 260 dwords, i.e. 4 banks further per k.  Stores of a
+// k-contiguous operand (16 lanes on 16 different k, same row index) then hit 16 different bank
+// groups, and the MFMA operand reads pair lane groups whose k differ by 8 (= 32 banks): MFMA
+// number kk of a K step multiplies k = {kk, kk+8, kk+4, kk+12}, the same set for both operands.
 // The kernel is launched on every call and returns at once unless the verdict selected it.
 #include "oz_internal.h"
 
@@ -16,7 +20,7 @@ namespace oz {
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int kDM = 128, kDN = 128, kDK = 16;
-constexpr int kDPad = 4;                        // doubles of padding per LDS row
+constexpr int kDPad = 2;                        // doubles of padding per LDS row (see the bank note below)
 constexpr int kDLd = kDM + kDPad;
 
 // tile loader: 16 (k) x 128 (r) elements of an operand whose element (r, l) is at
@@ -58,12 +62,28 @@ template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, bool EDGE>
 __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     const Record* rec, int64_t m, int64_t n, int64_t k, double alpha, const double* __restrict__ A,
     int64_t a_sr, int64_t a_sl, const double* __restrict__ B, int64_t b_sr, int64_t b_sl, double beta,
-    double* __restrict__ C, int64_t ldc, int ntm) {
+    double* __restrict__ C, int64_t ldc, int ntm, int ntn) {
     __shared__ double At[2][kDK * kDLd];
     __shared__ double Bt[2][kDK * kDLd];
     if (rec && !rec->res.fallback) return;
 
-    const int64_t i0 = int64_t(blockIdx.x % ntm) * kDM, j0 = int64_t(blockIdx.x / ntm) * kDN;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous range of a tile
+    // order in which 64 consecutive tiles (what an XCD runs at a time: 32 CUs, two workgroups each)
+    // form an 8 x 8 block, so they share 16 panels in that XCD's L2.
+    int ti, tj;
+    {
+        const int total = ntm * ntn;
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int per = total >> 3, rem = total & 7;
+        const int lin = xcd * per + min(xcd, rem) + slot;
+        constexpr int GW = 8;
+        const int panel = lin / (GW * ntm);
+        const int in_panel = lin - panel * GW * ntm;
+        const int w = min(GW, ntn - panel * GW);
+        ti = in_panel / w;
+        tj = panel * GW + in_panel % w;
+    }
+    const int64_t i0 = int64_t(ti) * kDM, j0 = int64_t(tj) * kDN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wi = wave & 1, wj = wave >> 1;
 
@@ -109,7 +129,8 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         const double* lb = Bt[buf] + wj * 64 + (lane & 15);
 #pragma unroll
         for (int kk = 0; kk < kDK / 4; ++kk) {
-            const int kr = (kk * 4 + (lane >> 4)) * kDLd;
+            const int g = lane >> 4;
+            const int kr = (kk + 8 * (g & 1) + 4 * (g >> 1)) * kDLd;
             double fa[4], fb[4];
 #pragma unroll
             for (int f = 0; f < 4; ++f) { fa[f] = la[kr + f * 16]; fb[f] = lb[kr + f * 16]; }
@@ -158,9 +179,9 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
 #define OZ_DG(AC, BC)                                                                                          \
     {                                                                                                          \
         if (edge) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, true>), grid, block, 0, st, rec, m, n, k, alpha, A, \
-                                     a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm);                            \
+                                     a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);                       \
         else hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, false>), grid, block, 0, st, rec, m, n, k, alpha, A, \
-                                a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm);                                 \
+                                a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);                            \
     }
     if (ac && bc) OZ_DG(true, true)
     else if (ac && !bc) OZ_DG(true, false)
