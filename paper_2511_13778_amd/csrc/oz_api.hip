@@ -11,6 +11,7 @@
 
 struct oz_handle {
     int device;
+    int num_cu;
     oz_heuristic_t hm;
     // stage timing
     int prof_calls;       // calls still to be recorded
@@ -77,6 +78,7 @@ bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, 
     p.esc_block = o.esc_block > 0 ? o.esc_block : kDefaultEscBlock;
     p.G = int((p.k + p.esc_block - 1) / p.esc_block);
     if (p.G < 1) p.G = 1;
+    p.num_cu = h.num_cu;
     return true;
 }
 
@@ -178,6 +180,7 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
     oz_handle* h = new (std::nothrow) oz_handle();
     if (!h) return OZ_ERR_ARG;
     h->device = device;
+    h->num_cu = prop.multiProcessorCount;
     // measured on MI355X at 8192^3: slice GEMM 2.45 POP/s, native FP64 GEMM 66 TFLOP/s, streaming
     // kernels about 4 TB/s, launch overhead of the ten kernels of a call
     h->hm.int8_ops_per_ns = 2450000;

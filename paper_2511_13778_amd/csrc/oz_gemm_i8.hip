@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                                                       const int8_t* __restrict__ Bs,
                                                       int32_t* __restrict__ P, int64_t mp,
                                                       int64_t np, int64_t kp, int s_cap,
-                                                      Record* rec) {
+                                                      Record* rec, int full_chip) {
     extern __shared__ __align__(16) uint8_t lds[];
     if (rec->res.fallback) return;
     const int S = rec->res.slices_used;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     const int sync_round = slot / kRoundTiles;
     const int sync_members = min(kRoundTiles, xcd_tiles - sync_round * kRoundTiles);
     const int sync_base = sync_round * kRoundTiles * sync_steps;
-    const bool sync_on = xcd_tiles > kRoundTiles && sync_members > 1;
+    const bool sync_on = full_chip && xcd_tiles > kRoundTiles && sync_members > 1;
     int sync_q = 0;
     if (sync_on) round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members);
 
@@ -284,15 +284,15 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 #undef OZ_READ_B
 
 void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        attr_set = true;
-    }
+    // the attribute is per device and cheap to set; no process-wide cache that a second device would miss
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     const unsigned tiles = unsigned((p.mp / kBM) * (p.np / kBN));
+    // the workgroup-to-XCD reasoning behind the in-step waits holds for the whole chip only
+    // (8 XCDs of 32 CUs); a partitioned device runs the same kernel without them
+    const int full_chip = p.num_cu == 8 * kRoundTiles ? 1 : 0;
     hipLaunchKernelGGL(gemm_i8_kernel, dim3(tiles), dim3(256), kGemmLds, st, w.As, w.Bs, w.P, p.mp, p.np,
-                       p.kp, p.s_cap, w.rec);
+                       p.kp, p.s_cap, w.rec, full_chip);
 }
 
 }  // namespace oz

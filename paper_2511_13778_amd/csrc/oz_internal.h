@@ -46,6 +46,7 @@ struct Problem {
     int64_t kblk;          // k-block length (multiple of kKPad)
     int32_t esc_block;     // b
     int32_t G;             // ceil(k / b)
+    int32_t num_cu;        // compute units of the device
 };
 
 struct Workspace {

@@ -136,6 +136,16 @@ def test_config4_short_k_unguarded(lib):
     sampled_parity(g, h, A, B, 1.0, 0.0, None, "unguarded", 55, None)
 
 
+def test_many_tiles_long_k(lib):
+    # 18 x 18 = 324 tiles of 256 x 256: more than the 256 workgroups the chip runs at a time, so the
+    # slice GEMM's workgroups take the in-step waits (a full round of 32 per XCD and a partial one),
+    # and k = 12288 adds the waits after every anti-diagonal
+    g, h = lib
+    A, B, Cin = wl.lognormal_spread(4608, 12288, 4608, 1.0, seed=23, with_c=True)
+    res, ratio = sampled_parity(g, h, A, B, 1.5, 0.5, Cin, "unguarded", 55, None, nsample=32)
+    assert res.slices_used == 7
+
+
 def test_reproducible_across_calls(lib):
     # integer accumulation is order-free and the FP64 order is fixed: C is bit-identical run to run
     g, h = lib
