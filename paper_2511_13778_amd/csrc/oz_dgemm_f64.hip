@@ -40,11 +40,15 @@ __device__ __forceinline__ void dg_load(double (&v)[8], const double* __restrict
         v[q] = (r < rows && l < k) ? x : 0.0;
     }
 }
-// interior tiles (no bounds to check): p points at this thread's first element of the K step,
-// the other seven are q*qstep elements further on
-__device__ __forceinline__ void dg_load_interior(double (&v)[8], const double* __restrict__ p, int64_t qstep) {
+// interior tiles (no bounds to check): `u` is the wave-uniform address of the K step of this tile,
+// `vo` this thread's byte offset inside it (fixed for the whole kernel), the eight elements of a
+// thread are qstep elements apart.  Uniform base + 32-bit lane offset keeps the addresses in
+// scalar registers.
+__device__ __forceinline__ void dg_load_interior(double (&v)[8], const double* __restrict__ u, uint32_t vo,
+                                                 int64_t qstep) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = p[q * qstep];
+    for (int q = 0; q < 8; ++q)
+        v[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(u + q * qstep) + vo);
 }
 
 template <bool ROWS_CONTIG>
@@ -95,58 +99,101 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
 
     double va[8], vb[8];
     // EDGE == false: m, n multiples of the tile and k a multiple of the K step
-    const double* pa = A + (A_ROWS_CONTIG ? (i0 + (threadIdx.x & 127)) * a_sr + (threadIdx.x >> 7) * a_sl
-                                          : (i0 + (threadIdx.x >> 4)) * a_sr + (threadIdx.x & 15) * a_sl);
-    const double* pb = B + (B_ROWS_CONTIG ? (j0 + (threadIdx.x & 127)) * b_sr + (threadIdx.x >> 7) * b_sl
-                                          : (j0 + (threadIdx.x >> 4)) * b_sr + (threadIdx.x & 15) * b_sl);
+    const double* ua = A + i0 * a_sr;   // wave-uniform: start of this tile's rows at k = 0
+    const double* ub = B + j0 * b_sr;
+    const uint32_t voa = uint32_t(A_ROWS_CONTIG ? (threadIdx.x & 127) * a_sr + (threadIdx.x >> 7) * a_sl
+                                                : (threadIdx.x >> 4) * a_sr + (threadIdx.x & 15) * a_sl) * 8u;
+    const uint32_t vob = uint32_t(B_ROWS_CONTIG ? (threadIdx.x & 127) * b_sr + (threadIdx.x >> 7) * b_sl
+                                                : (threadIdx.x >> 4) * b_sr + (threadIdx.x & 15) * b_sl) * 8u;
     const int64_t qa = A_ROWS_CONTIG ? 2 * a_sl : 16 * a_sr, qb = B_ROWS_CONTIG ? 2 * b_sl : 16 * b_sr;
     if (EDGE) {
         dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, 0, k);
         dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, 0, k);
     } else {
-        dg_load_interior(va, pa, qa);
-        dg_load_interior(vb, pb, qb);
+        dg_load_interior(va, ua, voa, qa);
+        dg_load_interior(vb, ub, vob, qb);
     }
     dg_store<A_ROWS_CONTIG>(va, At[0]);
     dg_store<B_ROWS_CONTIG>(vb, Bt[0]);
     __syncthreads();
 
+    // fragments of MFMA step kk of the K step in LDS buffer `b`: lane group g = lane/16 multiplies
+    // k = kk + 8*(g&1) + 4*(g>>1) (see the bank note at the top)
+    const int g = lane >> 4;
+    const int krow = (8 * (g & 1) + 4 * (g >> 1)) * kDLd;
+    const int la_off = wi * 64 + (lane & 15) + krow, lb_off = wj * 64 + (lane & 15) + krow;
+#define OZ_DG_READ(fa, fb, b, kk)                                                              \
+    _Pragma("unroll") for (int f = 0; f < 4; ++f) {                                            \
+        fa[f] = At[b][la_off + (kk) * kDLd + f * 16];                                          \
+        fb[f] = Bt[b][lb_off + (kk) * kDLd + f * 16];                                          \
+    }
+#define OZ_DG_MFMA(fa, fb)                                                                     \
+    _Pragma("unroll") for (int fj = 0; fj < 4; ++fj) _Pragma("unroll") for (int fi = 0; fi < 4; ++fi) \
+        acc[fj][fi] = __builtin_amdgcn_mfma_f64_16x16x4f64(fb[fj], fa[fi], acc[fj][fi], 0, 0, 0);
+
+    // Software pipeline of one K step (16 k = 4 MFMA steps of 16 MFMAs), arranged so that the matrix
+    // unit always has work.  Interior tiles run it branch-free (the last K step loads its own tile
+    // again and stores it where nobody reads it), which leaves one scheduling region per half, and
+    // the group barriers below fix the interleave inside it:
+    //   step 0: one global load of the next tile per MFMA          (fragments of step 1 are read first)
+    //   step 1: MFMAs only                                         (fragments of step 2 are read first)
+    //   step 2: one LDS store of the next tile per MFMA            (fragments of step 3 are read first)
+    //   barrier: next tile visible, nobody reads this buffer any more (step 3 is in registers)
+    //   step 3: MFMAs; they cover the barrier and the first fragment read of the next tile
+    double xa[4], xb[4], ya[4], yb[4];
     int buf = 0;
+    OZ_DG_READ(xa, xb, 0, 0);
     for (int64_t l0 = 0; l0 < k; l0 += kDK) {
         const bool have_next = l0 + kDK < k;
-        if (have_next) {
-            if (EDGE) {
+        if (EDGE) {
+            if (have_next) {
                 dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
                 dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
-            } else {
-                pa += kDK * a_sl;
-                pb += kDK * b_sl;
-                dg_load_interior(va, pa, qa);
-                dg_load_interior(vb, pb, qb);
             }
+        } else {
+            ua += have_next ? kDK * a_sl : 0;
+            ub += have_next ? kDK * b_sl : 0;
+            dg_load_interior(va, ua, voa, qa);
+            dg_load_interior(vb, ub, vob, qb);
         }
-        const double* la = At[buf] + wi * 64 + (lane & 15);
-        const double* lb = Bt[buf] + wj * 64 + (lane & 15);
-#pragma unroll
-        for (int kk = 0; kk < kDK / 4; ++kk) {
-            const int g = lane >> 4;
-            const int kr = (kk + 8 * (g & 1) + 4 * (g >> 1)) * kDLd;
-            double fa[4], fb[4];
-#pragma unroll
-            for (int f = 0; f < 4; ++f) { fa[f] = la[kr + f * 16]; fb[f] = lb[kr + f * 16]; }
-#pragma unroll
-            for (int fj = 0; fj < 4; ++fj)
-#pragma unroll
-                for (int fi = 0; fi < 4; ++fi)
-                    acc[fj][fi] = __builtin_amdgcn_mfma_f64_16x16x4f64(fb[fj], fa[fi], acc[fj][fi], 0, 0, 0);
-        }
-        if (have_next) {
+        OZ_DG_READ(ya, yb, buf, 1);
+        OZ_DG_MFMA(xa, xb);
+        OZ_DG_READ(xa, xb, buf, 2);
+        OZ_DG_MFMA(ya, yb);
+        OZ_DG_READ(ya, yb, buf, 3);
+        if (!EDGE || have_next) {
             dg_store<A_ROWS_CONTIG>(va, At[buf ^ 1]);
             dg_store<B_ROWS_CONTIG>(vb, Bt[buf ^ 1]);
         }
+        OZ_DG_MFMA(xa, xb);
+        if (!EDGE) {
+            // masks: 0x008 MFMA, 0x020 global load, 0x100 LDS read, 0x200 LDS write
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            }
+        }
         __syncthreads();
         buf ^= 1;
+        if (!EDGE || have_next) { OZ_DG_READ(xa, xb, buf, 0); }
+        OZ_DG_MFMA(ya, yb);
+        if (!EDGE) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        }
     }
+#undef OZ_DG_READ
+#undef OZ_DG_MFMA
 
     // result register r of tile (fj, fi): j = fj*16 + 4*r + lane/16, i = fi*16 + lane%16
 #pragma unroll
