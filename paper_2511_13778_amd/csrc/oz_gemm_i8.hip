@@ -22,7 +22,12 @@
 //  * The B-slices feed the MFMA's row operand and the A-slices its column operand, so the lane
 //    index of the result runs along i and the stores to P (i contiguous) coalesce.
 //  * Workgroup ids are remapped so that the tiles resident on one XCD form a compact block and
-//    share their A and B panels in that XCD's L2.
+//    share their A and B panels in that XCD's L2; the workgroups of such a block wait for each
+//    other (bounded) so that they stay within what L2 holds.
+//  * One wave per SIMD, so nothing hides an instruction that delays the next MFMA: at most one
+//    LDS read or one tile transfer (three instructions) sits between two MFMAs, tile addresses
+//    advance by one add per K step (the full address is recomputed only when the slice pair
+//    changes), and the workgroup barrier of a K step is followed by four MFMAs that cover it.
 #include "oz_internal.h"
 
 namespace oz {
@@ -79,14 +84,16 @@ __device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int& ti, int&
     tj = panel * GW + in_panel % w;
 }
 
-// 64 lanes x 16 B from global memory into LDS: lane l's 16 bytes land at lds_addr + 16*l.
-// The LDS byte address travels in M0.  The compiler does not see this as a memory access, so
-// completion is awaited with explicit s_waitcnt vmcnt(...) below.
-// The global address is a wave-uniform base (scalar registers) plus a per-lane byte offset, so
-// stepping through the tiles costs scalar arithmetic only.
+// 64 lanes x 16 B from global memory into LDS: lane l's 16 bytes land at lds_addr + LDS_IMM + 16*l.
+// The LDS byte address travels in M0 (set by the scalar add).  The compiler does not see this as a
+// memory access, so completion is awaited with explicit s_waitcnt vmcnt(...) below.
+// The global address is a wave-uniform base (scalar registers) plus a per-lane byte offset
+// (lane position plus the k chunk's distance, loop-invariant), so stepping through the tiles
+// costs two scalar adds per K step.
+template <int LDS_IMM>
 __device__ __forceinline__ void dma16(const uint8_t* gbase, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(gbase) : "memory");
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(gbase), "n"(LDS_IMM) : "memory", "scc");
 }
 
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__ As,
@@ -149,24 +156,37 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     const uint8_t* gA = reinterpret_cast<const uint8_t*>(As) + (i0 + wave * 64) * 16;   // wave-uniform
     const uint8_t* gB = reinterpret_cast<const uint8_t*>(Bs) + (j0 + wave * 64) * 16;
     const uint32_t lane_off = uint32_t(lane) * 16;
+    // per-lane byte offsets of the four k chunks of a tile (chunk q is q*rows*16 bytes further on)
+    uint32_t offA[4], offB[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        offA[q] = lane_off + uint32_t(q) * uint32_t(mp) * 16u;
+        offB[q] = lane_off + uint32_t(q) * uint32_t(np) * 16u;
+    }
     const int64_t planeA = kp * mp, planeB = kp * np;   // bytes per slice plane
 
-    // addresses of the next tile to fetch (8 transfers per wave: 4 k chunks of A, 4 of B)
-    const uint8_t* pa;
-    const uint8_t* pb;
+    // addresses of the next tile to fetch (8 transfers per wave: 4 k chunks of A, 4 of B).  The
+    // pointers advance by one K step per tile; only when the pair changes are they recomputed from
+    // the iterator (once per k-block length, outside the common path).
+    const uint8_t* pa = gA;
+    const uint8_t* pb = gB;
+    const int64_t stepA = int64_t(kBK) * mp, stepB = int64_t(kBK) * np;   // bytes per K step
     uint32_t la;
 #define OZ_TILE_ADDR()                                                                           \
-    {                                                                                            \
-        const int64_t kc = (int64_t(nkb_) * kblk) / 16 + int64_t(nkt) * (kBK / 16);              \
-        pa = gA + int64_t(ns) * planeA + kc * mp * 16;                                           \
-        pb = gB + int64_t(nd - ns) * planeB + kc * np * 16;                                      \
-        la = lds_base + issue_stage * kStageBytes + wave * 1024;                                 \
-    }
-// transfer number x (0..7) of the tile addressed by OZ_TILE_ADDR
+    { la = lds_base + issue_stage * kStageBytes + wave * 1024; }
+// transfer number x (0..7) of the tile addressed by pa / pb / la
 #define OZ_DMA(x)                                                                                \
     {                                                                                            \
-        if ((x) & 1) dma16(pb + ((x) >> 1) * np * 16, lane_off, la + kBM * kBK + ((x) >> 1) * (kBN * 16)); \
-        else dma16(pa + ((x) >> 1) * mp * 16, lane_off, la + ((x) >> 1) * (kBM * 16));           \
+        switch (x) {                                                                             \
+            case 0: dma16<0 * (kBM * 16)>(pa, offA[0], la); break;                                   \
+            case 1: dma16<kBM * kBK + 0 * (kBN * 16)>(pb, offB[0], la); break;                       \
+            case 2: dma16<1 * (kBM * 16)>(pa, offA[1], la); break;                                   \
+            case 3: dma16<kBM * kBK + 1 * (kBN * 16)>(pb, offB[1], la); break;                       \
+            case 4: dma16<2 * (kBM * 16)>(pa, offA[2], la); break;                                   \
+            case 5: dma16<kBM * kBK + 2 * (kBN * 16)>(pb, offB[2], la); break;                       \
+            case 6: dma16<3 * (kBM * 16)>(pa, offA[3], la); break;                                   \
+            default: dma16<kBM * kBK + 3 * (kBN * 16)>(pb, offB[3], la); break;                      \
+        }                                                                                        \
     }
 #define OZ_TILE_ADVANCE()                                                                        \
     {                                                                                            \
@@ -181,6 +201,12 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                     nxt_ktc = kt_count(nkb_);                                                    \
                 }                                                                                \
             }                                                                                    \
+            const int64_t kc = (int64_t(nkb_) * kblk) / 16;                                      \
+            pa = gA + int64_t(ns) * planeA + kc * mp * 16;                                       \
+            pb = gB + int64_t(nd - ns) * planeB + kc * np * 16;                                  \
+        } else {                                                                                 \
+            pa += stepA;                                                                         \
+            pb += stepB;                                                                         \
         }                                                                                        \
     }
 #define OZ_ISSUE_TILE()                                                                          \
@@ -222,30 +248,40 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                 // invariant here: transfers of the next three tiles are in flight (24 per wave);
                 // fragments of sub-step 0 of the current tile are in fa0/fb0
                 // first half: MFMAs of sub-step 0; the LDS reads of sub-step 1 ride along
+                // first half: MFMAs of sub-step 0 (16); one LDS read of sub-step 1 after each of the
+                // first eight, so that all have returned well before the barrier
 #pragma unroll
-                for (int g = 0; g < 8; ++g) {
-                    if (g < 4) { OZ_READ_A(fa1, stage, 1, g); OZ_READ_B(fb1, stage, 1, g); }
+                for (int q = 0; q < 12; ++q) {
+                    OZ_MFMA(fa0, fb0, q >> 2, q & 3);
                     __builtin_amdgcn_sched_barrier(0);
-                    OZ_MFMA(fa0, fb0, g >> 1, (g & 1) * 2);
-                    OZ_MFMA(fa0, fb0, g >> 1, (g & 1) * 2 + 1);
-                    __builtin_amdgcn_sched_barrier(0);
+                    if (q < 8) {
+                        if (q & 1) { OZ_READ_B(fb1, stage, 1, q >> 1); } else { OZ_READ_A(fa1, stage, 1, q >> 1); }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
                 // next tile landed (own transfers), every LDS read of this tile returned; after the
-                // barrier that holds for all waves, so this stage may be overwritten
+                // barrier that holds for all waves, so this stage may be overwritten.  The last four
+                // MFMAs of the first half cover the barrier.
                 asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
                 const int next_stage = (stage + 1) & (kStages - 1);
                 OZ_TILE_ADDR();
-                // second half: MFMAs of sub-step 1; one transfer of the tile three stages ahead is
-                // issued per MFMA pair, so a full memory queue delays at most one pair; the LDS
-                // reads of the next tile's sub-step 0 ride along
+#pragma unroll
+                for (int q = 12; q < 16; ++q) {
+                    OZ_MFMA(fa0, fb0, q >> 2, q & 3);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // second half: MFMAs of sub-step 1; after each one either an LDS read of the next
+                // tile's sub-step 0 or a transfer of the tile three stages ahead
 #pragma unroll
                 for (int g = 0; g < 8; ++g) {
-                    if (g < 4) { OZ_READ_A(fa0, next_stage, 0, g); OZ_READ_B(fb0, next_stage, 0, g); }
-                    __builtin_amdgcn_sched_barrier(0);
                     OZ_MFMA(fa1, fb1, g >> 1, (g & 1) * 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (g & 1) { OZ_READ_B(fb0, next_stage, 0, g >> 1); } else { OZ_READ_A(fa0, next_stage, 0, g >> 1); }
+                    __builtin_amdgcn_sched_barrier(0);
                     OZ_MFMA(fa1, fb1, g >> 1, (g & 1) * 2 + 1);
                     __builtin_amdgcn_sched_barrier(0);
                     OZ_DMA(g);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 OZ_TILE_ADVANCE();
                 stage = next_stage;
