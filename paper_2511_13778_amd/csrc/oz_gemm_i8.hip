@@ -235,7 +235,9 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     OZ_ISSUE_TILE();
     OZ_ISSUE_TILE();
     asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-    OZ_ISSUE_TILE();
+    OZ_TILE_ADDR();
+#pragma unroll
+    for (int x = 0; x < 8; ++x) OZ_DMA(x);   // the iterator moves on in the first half of the loop body
     v4i fa0[4], fb0[4], fa1[4], fb1[4];
     int stage = 0;
     OZ_READ_FRAGS(fa0, fb0, stage, 0);
@@ -256,6 +258,10 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                     __builtin_amdgcn_sched_barrier(0);
                     if (q < 8) {
                         if (q & 1) { OZ_READ_B(fb1, stage, 1, q >> 1); } else { OZ_READ_A(fa1, stage, 1, q >> 1); }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (q == 9) {   // a gap without memory work: move the iterator past the tile issued last
+                        OZ_TILE_ADVANCE();
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -283,7 +289,6 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                     OZ_DMA(g);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                OZ_TILE_ADVANCE();
                 stage = next_stage;
             }
 
