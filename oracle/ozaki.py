@@ -190,8 +190,8 @@ def kept_pairs(S: int):
 class HeuristicModel:
     """Integer cost model for "emulation slower than FP64?" (parity unpinned: own constants).
     Rates in operations per nanosecond, fixed cost in nanoseconds, bandwidth in bytes/ns."""
-    int8_ops_per_ns: int = 2450000
-    fp64_flops_per_ns: int = 66000
+    int8_ops_per_ns: int = 2650000
+    fp64_flops_per_ns: int = 71000
     bytes_per_ns: int = 4000
     fixed_ns: int = 60000
 

@@ -181,10 +181,10 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
     if (!h) return OZ_ERR_ARG;
     h->device = device;
     h->num_cu = prop.multiProcessorCount;
-    // measured on MI355X at 8192^3: slice GEMM 2.45 POP/s, native FP64 GEMM 66 TFLOP/s, streaming
+    // measured on MI355X at 8192^3: slice GEMM 2.65 POP/s, native FP64 GEMM 71 TFLOP/s, streaming
     // kernels about 4 TB/s, launch overhead of the ten kernels of a call
-    h->hm.int8_ops_per_ns = 2450000;
-    h->hm.fp64_flops_per_ns = 66000;
+    h->hm.int8_ops_per_ns = 2650000;
+    h->hm.fp64_flops_per_ns = 71000;
     h->hm.bytes_per_ns = 4000;
     h->hm.fixed_ns = 60000;
     h->prof_calls = 0;
