@@ -72,14 +72,34 @@ __device__ __forceinline__ void emit_slices(const Fixed (&f)[16], int S, int8_t*
 
 // Up to 8 slices the whole fixed-point value fits one 64-bit word, and the carry chain of the remap
 // collapses into one addition: with BIAS = 0x80 in every sub-leading byte, the digits are the bytes
-// of X + BIAS with the top bit of every sub-leading byte flipped.  Byte b of 16 values is gathered
-// into four dwords with byte permutes (three per dword).
-__device__ __forceinline__ void emit_slices_64(const Fixed (&f)[16], int S, int8_t* dst, int64_t slice_stride) {
+// of X + BIAS with the top bit of every sub-leading byte flipped.
+//
+// X for S <= 8 without branches: with sh = max(field,1) - 1075 + q (q = 8S - 3 - e_row) it is
+// sM << sh or sM >> -sh (arithmetic: rounds toward -infinity), both computed and one selected;
+// shift counts are clamped to 63 (a left shift beyond the word only happens for Inf/NaN input in
+// unguarded mode).  Zeros, all-zero rows and padding have sM = 0 and need no special case.
+__device__ __forceinline__ uint64_t biased_fixed64(uint64_t bits, int q_minus_1075, uint64_t bias) {
+    const uint64_t mag = bits & 0x7FFFFFFFFFFFFFFFull;
+    const int field = int(mag >> 52);
+    const uint64_t frac = mag & 0x000FFFFFFFFFFFFFull;
+    const uint64_t M = field ? (frac | 0x0010000000000000ull) : frac;
+    const uint64_t sgn = uint64_t(int64_t(bits) >> 63);              // all ones for negative entries
+    const int64_t sM = int64_t((M ^ sgn) - sgn);
+    const int sh = max(field, 1) + q_minus_1075;
+    const int64_t left = sM << min(max(sh, 0), 63);
+    const int64_t right = sM >> min(max(-sh, 0), 63);
+    return uint64_t(sh >= 0 ? left : right) + bias;
+}
+
+// Byte b of 16 values is gathered into four dwords with byte permutes (three per dword).
+__device__ __forceinline__ void emit_slices_64(const uint64_t (&bits)[16], int e_row, int S, int8_t* dst,
+                                               int64_t slice_stride) {
     const uint64_t bias = S >= 2 ? (0x8080808080808080ull >> (8 * (9 - S))) : 0ull;
+    const int q = 8 * S - 2 - kHeadroomBits - (e_row > kExpAllZero ? e_row : 0) - 1075;
     uint32_t lo[16], hi[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        const uint64_t y = (uint64_t(f[e].W) << min(f[e].o, 63)) + bias;
+        const uint64_t y = biased_fixed64(bits[e], q, bias);
         lo[e] = uint32_t(y);
         hi[e] = uint32_t(y >> 32);
     }
@@ -107,9 +127,16 @@ __device__ __forceinline__ void emit_slices_64(const Fixed (&f)[16], int S, int8
     }
 }
 
-__device__ __forceinline__ void emit(const Fixed (&f)[16], int S, int8_t* dst, int64_t slice_stride) {
-    if (S <= 8) emit_slices_64(f, S, dst, slice_stride);
-    else emit_slices(f, S, dst, slice_stride);
+__device__ __forceinline__ void emit(const uint64_t (&bits)[16], int e_row, int S, int8_t* dst,
+                                     int64_t slice_stride) {
+    if (S <= 8) {
+        emit_slices_64(bits, e_row, S, dst, slice_stride);
+    } else {
+        Fixed f[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) f[e] = fixed_point(bits[e], e_row, S);
+        emit_slices(f, S, dst, slice_stride);
+    }
 }
 
 constexpr int kSliceChunksPerWg = 4;
@@ -124,17 +151,20 @@ __global__ __launch_bounds__(256) void slice_rows_contig_kernel(
     const int64_t r = int64_t(blockIdx.x) * 256 + threadIdx.x;
     const int er = e_row[r];
     const int64_t slice_stride = kp * rows_p;      // bytes per slice plane
-    const uint64_t* src = reinterpret_cast<const uint64_t*>(X) + r;
+    // loads are unconditional at clamped addresses (rows >= 1 and k >= 1 here); out-of-range
+    // elements are then replaced by zero, so the loop has no divergent branches
+    const bool row_ok = r < rows;
+    const uint64_t* src = reinterpret_cast<const uint64_t*>(X) + (row_ok ? r : rows - 1);
     for (int cc = 0; cc < kSliceChunksPerWg; ++cc) {
         const int64_t c = int64_t(blockIdx.y) * kSliceChunksPerWg + cc;
-        Fixed f[16];
+        uint64_t bits[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int64_t l = c * 16 + e;
-            const uint64_t bits = (r < rows && l < k) ? src[l * stride_l] : 0ull;
-            f[e] = fixed_point(bits, er, S);
+            const uint64_t x = src[(l < k ? l : k - 1) * stride_l];
+            bits[e] = (row_ok && l < k) ? x : 0ull;
         }
-        emit(f, S, out + (c * rows_p + r) * 16, slice_stride);
+        emit(bits, er, S, out + (c * rows_p + r) * 16, slice_stride);
     }
 }
 
@@ -156,18 +186,19 @@ __global__ __launch_bounds__(256) void slice_k_contig_kernel(
         for (int it = 0; it < 16; ++it) {
             const int rr = rr0 + it * 4;
             const int64_t r = r0 + rr, l = l0 + ll;
-            T[rr][ll] = (r < rows && l < k) ? src[r * stride_r + l] : 0ull;
+            const uint64_t x = src[(r < rows ? r : rows - 1) * stride_r + (l < k ? l : k - 1)];
+            T[rr][ll] = (r < rows && l < k) ? x : 0ull;
         }
     }
     __syncthreads();
     const int rr = threadIdx.x & 63, cc = threadIdx.x >> 6;
     const int64_t r = r0 + rr;
     const int er = e_row[r];
-    Fixed f[16];
+    uint64_t bits[16];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) f[e] = fixed_point(T[rr][cc * 16 + e], er, S);
+    for (int e = 0; e < 16; ++e) bits[e] = T[rr][cc * 16 + e];
     const int64_t c = l0 / 16 + cc;
-    emit(f, S, out + (c * rows_p + r) * 16, kp * rows_p);
+    emit(bits, er, S, out + (c * rows_p + r) * 16, kp * rows_p);
 }
 
 void launch_slice(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l, int64_t rows,
