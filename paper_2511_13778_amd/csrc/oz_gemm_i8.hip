@@ -47,7 +47,8 @@ static_assert(kDmaPerStage == 8, "the vmcnt immediates below assume 8 DMA instru
 
 constexpr int kRoundTiles = 32;       // workgroups an XCD runs at a time: 32 CUs, one workgroup each
 constexpr int kMaxSyncSpins = 8192;   // upper bound of the wait for the other workgroups of a round
-constexpr int kMidSyncMinK = 12288;   // from this k on, workgroups also wait after every anti-diagonal
+constexpr int kMidSyncMinK = 12288;
+constexpr int kMinSplitSteps = 8;     // a part of a split k range keeps at least this many K steps   // from this k on, workgroups also wait after every anti-diagonal
 
 // Waits (bounded) until `target` workgroups have arrived at *counter.  The wait only improves cache
 // locality: correctness does not depend on it, and every wave gets past it whatever the other
@@ -68,14 +69,19 @@ __device__ __forceinline__ v4i as_v4i(const uint4& v) { return v4i{int(v.x), int
 // linear workgroup id -> tile coordinates.  Ids are dealt round-robin to the 8 XCDs by the
 // hardware; each XCD is given a contiguous range of a tile order in which 32 consecutive tiles
 // form a 4 (i) x 8 (j) block.
-__device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int& ti, int& tj, int& xcd, int& slot,
-                                        int& xcd_tiles) {
-    const int total = nti * ntj;
+// With a k split (zsplit > 1) a work unit is (tile, part of the k range); units are ordered part by
+// part, so the units an XCD runs together still are neighbouring tiles of the same k range.
+__device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int zsplit, int& ti, int& tj, int& z,
+                                        int& xcd, int& slot, int& xcd_tiles) {
+    const int tiles = nti * ntj;
+    const int total = tiles * zsplit;
     xcd = bid & 7;
     slot = bid >> 3;
     const int per = total >> 3, rem = total & 7;
     xcd_tiles = per + (xcd < rem ? 1 : 0);
-    const int lin = xcd * per + min(xcd, rem) + slot;
+    const int unit = xcd * per + min(xcd, rem) + slot;
+    z = unit / tiles;
+    const int lin = unit - z * tiles;
     constexpr int GW = 8;
     const int panel = lin / (GW * nti);
     const int in_panel = lin - panel * GW * nti;
@@ -100,7 +106,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                                                       const int8_t* __restrict__ Bs,
                                                       int32_t* __restrict__ P, int64_t mp,
                                                       int64_t np, int64_t kp, int s_cap,
-                                                      Record* rec, int full_chip) {
+                                                      Record* rec, int full_chip, int zsplit) {
     extern __shared__ __align__(16) uint8_t lds[];
     if (rec->res.fallback) return;
     const int S = rec->res.slices_used;
@@ -108,8 +114,18 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     const int64_t kblk = ((int64_t(1) << 17) - 1) / S / 256 * 256;
     const int nkb = int((kp + kblk - 1) / kblk);
 
-    int ti, tj, xcd, slot, xcd_tiles;
-    tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), ti, tj, xcd, slot, xcd_tiles);
+    int ti, tj, z, xcd, slot, xcd_tiles;
+    tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), zsplit, ti, tj, z, xcd, slot, xcd_tiles);
+
+    // This workgroup's share of the K steps: part z of zsplit equal parts of the whole k range (one
+    // part = everything when the call has enough tiles to fill the chip).  Parts of the same k-block
+    // add into the same int32 plane with integer atomics: exact and order-free, so the planes are
+    // the same as without a split.  The host zeroes P before the launch when zsplit > 1.
+    const int kt_total = int(kp / kBK);
+    const int kt_first = int(int64_t(kt_total) * z / zsplit);
+    const int kt_end = int(int64_t(kt_total) * (z + 1) / zsplit);
+    const int kt_per_block = int(kblk / kBK);
+    const int kb_first = kt_first / kt_per_block, kb_last = (kt_end - 1) / kt_per_block;
 
     // Keep the workgroups that share panels in step.  An XCD runs 32 workgroups at a time (one
     // per CU) and its tiles are ordered so that each such round is one 4x8 block.  The workgroups
@@ -119,7 +135,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     // this: hit rate 49 % instead of 81 %, 10 % more time; at k = 8192 the start of the tile is
     // enough and the extra waits would cost 1 %).  Arrival number q of a workgroup of round r waits
     // for 32*r*steps + (q+1)*members arrivals on the XCD's counter (earlier rounds are full rounds).
-    const int sync_steps = kp >= kMidSyncMinK ? nkb * S : 1;
+    const int sync_steps = (kp >= kMidSyncMinK && zsplit == 1) ? nkb * S : 1;
     const int sync_round = slot / kRoundTiles;
     const int sync_members = min(kRoundTiles, xcd_tiles - sync_round * kRoundTiles);
     const int sync_base = sync_round * kRoundTiles * sync_steps;
@@ -140,17 +156,15 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[a][b] = zero;
 
-    auto kt_count = [&](int kb) -> int {
-        const int64_t k0 = int64_t(kb) * kblk;
-        const int64_t k1 = (k0 + kblk < kp) ? k0 + kblk : kp;
-        return int((k1 - k0) / kBK);
-    };
+    // K steps [kt_lo(kb), kt_lo(kb) + kt_count(kb)) of k-block kb belong to this workgroup
+    auto kt_lo = [&](int kb) -> int { return max(kb * kt_per_block, kt_first); };
+    auto kt_count = [&](int kb) -> int { return min((kb + 1) * kt_per_block, kt_end) - kt_lo(kb); };
 
     // (nkb_, nd, ns, nkt) walks the (k-block, anti-diagonal, pair, K step) sequence ahead of the
     // compute, so the prefetch runs across pair and anti-diagonal boundaries without a bubble.
     // After the last tile it stays put: the surplus transfers land in stages nobody reads again.
-    int nkb_ = 0, nd = 0, ns = 0, nkt = 0;
-    int nxt_ktc = kt_count(0);
+    int nkb_ = kb_first, nd = 0, ns = 0, nkt = 0;
+    int nxt_ktc = kt_count(kb_first);
     int issue_stage = 0;
     const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) uint8_t*)lds));
     const uint8_t* gA = reinterpret_cast<const uint8_t*>(As) + (i0 + wave * 64) * 16;   // wave-uniform
@@ -168,8 +182,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     // addresses of the next tile to fetch (8 transfers per wave: 4 k chunks of A, 4 of B).  The
     // pointers advance by one K step per tile; only when the pair changes are they recomputed from
     // the iterator (once per k-block length, outside the common path).
-    const uint8_t* pa = gA;
-    const uint8_t* pb = gB;
+    const uint8_t* pa = gA + int64_t(kt_first) * (kBK / 16) * mp * 16;
+    const uint8_t* pb = gB + int64_t(kt_first) * (kBK / 16) * np * 16;
     const int64_t stepA = int64_t(kBK) * mp, stepB = int64_t(kBK) * np;   // bytes per K step
     uint32_t la;
 #define OZ_TILE_ADDR()                                                                           \
@@ -197,11 +211,11 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                 ns = 0;                                                                          \
                 if (++nd == S) {                                                                 \
                     nd = 0;                                                                      \
-                    if (++nkb_ == nkb) nkb_ = nkb - 1;                                           \
+                    if (++nkb_ > kb_last) nkb_ = kb_last;                                        \
                     nxt_ktc = kt_count(nkb_);                                                    \
                 }                                                                                \
             }                                                                                    \
-            const int64_t kc = (int64_t(nkb_) * kblk) / 16;                                      \
+            const int64_t kc = int64_t(kt_lo(nkb_)) * (kBK / 16);                                \
             pa = gA + int64_t(ns) * planeA + kc * mp * 16;                                       \
             pb = gB + int64_t(nd - ns) * planeB + kc * np * 16;                                  \
         } else {                                                                                 \
@@ -242,7 +256,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     int stage = 0;
     OZ_READ_FRAGS(fa0, fb0, stage, 0);
 
-    for (int kb = 0; kb < nkb; ++kb) {
+    for (int kb = kb_first; kb <= kb_last; ++kb) {
         const int ktc = kt_count(kb);
         for (int d = 0; d < S; ++d) {
             const int n_iter = (d + 1) * ktc;
@@ -304,7 +318,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                     for (int r = 0; r < 16; ++r) {
                         const int jl = fj * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                         const int il = fi * 32 + (lane & 31);
-                        dst[int64_t(jl) * mp + il] = acc[fj][fi][r];
+                        if (zsplit > 1) atomicAdd(&dst[int64_t(jl) * mp + il], acc[fj][fi][r]);
+                        else dst[int64_t(jl) * mp + il] = acc[fj][fi][r];
                     }
                     acc[fj][fi] = zero;
                 }
@@ -324,16 +339,37 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 #undef OZ_READ_A
 #undef OZ_READ_B
 
+// P = 0 before a launch whose workgroups add their parts of the k range into it
+__global__ __launch_bounds__(256) void zero_planes_kernel(int4* __restrict__ P, size_t n16, const Record* rec) {
+    if (rec->res.fallback) return;
+    const size_t t = size_t(blockIdx.x) * 256 + threadIdx.x;
+    if (t < n16) P[t] = make_int4(0, 0, 0, 0);
+}
+
 void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p) {
     // the attribute is per device and cheap to set; no process-wide cache that a second device would miss
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     const unsigned tiles = unsigned((p.mp / kBM) * (p.np / kBN));
+    // Too few tiles to fill the chip: split the k range so that about one workgroup per CU results,
+    // each part keeping at least kMinSplitSteps K steps.  The parts add into P with integer atomics.
+    const int64_t kt_total = p.kp / kBK;
+    int zsplit = 1;
+    if (tiles * 4 <= unsigned(p.num_cu) * 3) {
+        zsplit = int(p.num_cu / tiles);
+        if (zsplit > kt_total / kMinSplitSteps) zsplit = int(kt_total / kMinSplitSteps);
+        if (zsplit < 1) zsplit = 1;
+    }
+    if (zsplit > 1) {
+        const size_t words = size_t(p.nkb) * p.s_cap * p.np * p.mp;
+        hipLaunchKernelGGL(zero_planes_kernel, dim3(unsigned((words / 4 + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<int4*>(w.P), words / 4, w.rec);
+    }
     // the workgroup-to-XCD reasoning behind the in-step waits holds for the whole chip only
     // (8 XCDs of 32 CUs); a partitioned device runs the same kernel without them
     const int full_chip = p.num_cu == 8 * kRoundTiles ? 1 : 0;
-    hipLaunchKernelGGL(gemm_i8_kernel, dim3(tiles), dim3(256), kGemmLds, st, w.As, w.Bs, w.P, p.mp, p.np,
-                       p.kp, p.s_cap, w.rec, full_chip);
+    hipLaunchKernelGGL(gemm_i8_kernel, dim3(tiles * unsigned(zsplit)), dim3(256), kGemmLds, st, w.As, w.Bs, w.P,
+                       p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, zsplit);
 }
 
 }  // namespace oz
