@@ -191,7 +191,7 @@ class HeuristicModel:
     """Integer cost model for "emulation slower than FP64?" (parity unpinned: own constants).
     Rates in operations per nanosecond, fixed cost in nanoseconds, bandwidth in bytes/ns."""
     int8_ops_per_ns: int = 2650000
-    fp64_flops_per_ns: int = 71000
+    fp64_flops_per_ns: int = 66000
     bytes_per_ns: int = 4000
     fixed_ns: int = 60000
 
@@ -247,6 +247,18 @@ def verdict(mode: int, target_bits: int, max_bits: int, slices_override: int, in
             return Verdict(1, REASON_HEURISTIC, 0, esc, required, 0)
         return Verdict(0, REASON_NONE, S, esc, required, 0)
     raise ValueError("unknown mode")
+
+
+def shape_only_fallback(mode: int, target_bits: int, m: int, n: int, k: int,
+                        heuristic: HeuristicModel | None) -> bool:
+    """DYNAMIC mode with the heuristic on: the ESC is at least 1, so no input can get fewer than
+    slices_dynamic(target_bits, 1) slices; if the cost model already calls that count slower than
+    the native GEMM, the call goes native without scanning the operands (the record then holds
+    no ESC and no Inf/NaN flag).  Own choice within the section "Heuristic run time Selection"
+    (small problems fall back to native FP64 so that run time never drops below the baseline)."""
+    if mode != MODE_DYNAMIC or heuristic is None:
+        return False
+    return heuristic.emulation_slower(min(slices_dynamic(target_bits, 1), MAX_SLICES), m, n, k)
 
 
 # --------------------------------------------------------------------------------------
@@ -484,6 +496,8 @@ def emulated_dgemm(A: np.ndarray, B: np.ndarray, alpha: float = 1.0, beta: float
     if m == 0 or n == 0 or k == 0 or alpha == 0.0:     # BLAS convention: C <- beta*C
         out = np.zeros((m, n)) if beta == 0.0 else np.float64(beta) * np.asarray(C, dtype=np.float64)
         return Trace(Verdict(0, REASON_NONE, 0, -1, 0, 0), C=out)
+    if shape_only_fallback(mode, target_bits, m, n, k, heuristic):
+        return Trace(Verdict(1, REASON_HEURISTIC, 0, -1, 0, 0), C=native_gemm(alpha, A, B, beta, C))
     guarded = mode in (MODE_DYNAMIC, MODE_FORCED_GUARDED, MODE_FIXED_GUARDED)
     infnan = guarded and (has_inf_nan(A) or has_inf_nan(B))
     esc = esc_coarse(A, B, esc_block) if (guarded and not infnan) else -1

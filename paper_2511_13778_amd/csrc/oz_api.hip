@@ -181,10 +181,10 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
     if (!h) return OZ_ERR_ARG;
     h->device = device;
     h->num_cu = prop.multiProcessorCount;
-    // measured on MI355X at 8192^3: slice GEMM 2.65 POP/s, native FP64 GEMM 71 TFLOP/s, streaming
+    // measured on MI355X at 8192^3: slice GEMM 2.65 POP/s, native FP64 GEMM 66-72 TFLOP/s (the lower figure, reached at 4096^3, is used), streaming
     // kernels about 4 TB/s, launch overhead of the ten kernels of a call
     h->hm.int8_ops_per_ns = 2650000;
-    h->hm.fp64_flops_per_ns = 71000;
+    h->hm.fp64_flops_per_ns = 66000;
     h->hm.bytes_per_ns = 4000;
     h->hm.fixed_ns = 60000;
     h->prof_calls = 0;
@@ -305,6 +305,20 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
         launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
         clk.done(6);
         return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+    }
+
+    if (opts->mode == OZ_DYNAMIC && opts->heuristic) {
+        // the ESC is at least 1: no input gets fewer slices than this; if even that count is slower
+        // than the native GEMM by the cost model, the operands need not be scanned at all
+        int s_min = (opts->target_bits + 1 + 1 + kHeadroomBits + 7) / 8;
+        if (s_min > kMaxSlices) s_min = kMaxSlices;
+        if (emulation_slower(h->hm, s_min, m, n, k)) {
+            launch_verdict(st, w, p, *opts, h->hm, 3, result);
+            for (int s = 0; s <= 5; ++s) clk.done(s);
+            launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+            clk.done(6);
+            return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+        }
     }
 
     const bool guarded = opts->mode != OZ_FIXED_UNGUARDED;

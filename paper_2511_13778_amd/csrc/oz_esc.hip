@@ -259,7 +259,10 @@ __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int 
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     oz_result_t r;
     r.fallback = 0; r.reason = 0; r.slices_used = 0; r.esc = -1; r.required_bits = 0; r.infnan = 0;
-    if (kind == 2) {   // nothing to multiply (k == 0 or alpha == 0)
+    if (kind == 2 || kind == 3) {
+        // 2: nothing to multiply (k == 0 or alpha == 0); 3: the host's cost model says that no slice
+        // count this call could get beats the native GEMM, so nothing was scanned
+        if (kind == 3) { r.fallback = 1; r.reason = 3; }
         rec->res = r;
         if (user_result) *user_result = r;
         return;

@@ -77,7 +77,8 @@ void launch_scan(hipStream_t st, const double* X, int64_t stride_r, int64_t stri
                  int64_t rows, int64_t rows_p, const Problem& p, int16_t* tab, bool max_first,
                  int32_t* e_out, Record* rec, bool check_infnan);
 void launch_esc(hipStream_t st, const Workspace& w, const Problem& p);
-// kind: 0 unguarded, 1 guarded, 2 nothing to multiply (record says "emulated, 0 slices")
+// kind: 0 unguarded, 1 guarded, 2 nothing to multiply (record says "emulated, 0 slices"),
+// 3 native by the cost model alone (nothing scanned)
 void launch_verdict(hipStream_t st, const Workspace& w, const Problem& p, const oz_opts_t& o,
                     const oz_heuristic_t& hm, int kind, oz_result_t* user_result);
 void launch_slice(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l,

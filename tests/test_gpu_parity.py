@@ -307,10 +307,32 @@ def test_heuristic_sends_small_problems_native(lib):
     g, h = lib
     A, B = wl.uniform_pm1(48, 48, 48, seed=30)
     got, _, res = run_gpu(g, h, A, B, mode=g.OZ_DYNAMIC, max_bits=200, heuristic=1)
-    assert (res.fallback, res.reason) == (1, oz.REASON_HEURISTIC)
-    v = oz.verdict(oz.MODE_DYNAMIC, 53, 200, 0, False, res.esc, 48, 48, 48, oz.HeuristicModel())
-    assert v.reason == oz.REASON_HEURISTIC
+    # no slice count this shape could get beats the native GEMM: native without a scan
+    v = oz.emulated_dgemm(A, B, mode=oz.MODE_DYNAMIC, max_bits=200, heuristic=oz.HeuristicModel()).verdict
+    assert (v.fallback, v.reason, v.esc) == (1, oz.REASON_HEURISTIC, -1)
+    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan) == \
+           (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan)
     assert np.allclose(got, A @ B, rtol=0, atol=48 * 2.0 ** -53 * 48)
+
+
+def test_heuristic_after_the_esc(lib):
+    # a shape where 7 slices would pay but the ESC asks for more: scanned, then native by the heuristic
+    g, h = lib
+    A, B = wl.lognormal_spread(4096, 4096, 4096, 1.0, seed=31)
+    m = 4096
+    opts = g.make_opts(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=1)
+    gm = g.Gemm(h, m, m, m, opts)
+    dA, dB = g.to_colmajor(A), g.to_colmajor(B)
+    dC = torch.empty((m, m), dtype=torch.float64, device="cuda")
+    gm.run(dA, m, dB, m, dC, m)
+    torch.cuda.synchronize()
+    res = gm.result()
+    assert not oz.shape_only_fallback(oz.MODE_DYNAMIC, 53, m, m, m, oz.HeuristicModel())
+    v = oz.verdict(oz.MODE_DYNAMIC, 53, 200, 0, False, res.esc, m, m, m, oz.HeuristicModel())
+    assert res.esc > 1
+    assert (res.fallback, res.reason, res.slices_used, res.required_bits) == \
+           (v.fallback, v.reason, v.slices_used, v.required_bits)
+    assert (v.fallback, v.reason) == (1, oz.REASON_HEURISTIC)
 
 
 @pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512)])   # ragged path, interior fast path

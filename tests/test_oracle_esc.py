@@ -131,3 +131,22 @@ def test_verdict_table():
     assert V(oz.MODE_FIXED_UNGUARDED, 53, 55, 0, False, -1, 8, 8, 8).slices_used == 7
     assert V(oz.MODE_FIXED_UNGUARDED, 53, 55, 9, False, -1, 8, 8, 8).slices_used == 9
     assert V(oz.MODE_NATIVE, 53, 55, 0, False, -1, 8, 8, 8).reason == oz.REASON_NATIVE
+
+
+def test_shape_only_fallback_agrees_with_the_verdict():
+    # the pre-check may only fire where the full verdict would say "heuristic" for every possible ESC
+    hm = oz.HeuristicModel()
+    for n in (16, 256, 1024, 3000, 4096, 8192):
+        pre = oz.shape_only_fallback(oz.MODE_DYNAMIC, 53, n, n, n, hm)
+        best = oz.verdict(oz.MODE_DYNAMIC, 53, 200, 0, False, 1, n, n, n, hm)       # ESC = 1: fewest slices
+        assert pre == (best.reason == oz.REASON_HEURISTIC)
+        if pre:
+            for esc in (1, 5, 20, 60):
+                assert oz.verdict(oz.MODE_DYNAMIC, 53, 200, 0, False, esc, n, n, n, hm).reason == oz.REASON_HEURISTIC
+    assert oz.shape_only_fallback(oz.MODE_DYNAMIC, 53, 32, 32, 32, hm)
+    assert not oz.shape_only_fallback(oz.MODE_DYNAMIC, 53, 8192, 8192, 8192, hm)
+    assert not oz.shape_only_fallback(oz.MODE_DYNAMIC, 53, 32, 32, 32, None)          # heuristic off
+    assert not oz.shape_only_fallback(oz.MODE_FORCED_GUARDED, 53, 32, 32, 32, hm)   # other modes never
+    A = np.ones((8, 8)); A[0, 0] = np.inf
+    tr = oz.emulated_dgemm(A, np.ones((8, 8)), mode=oz.MODE_DYNAMIC, max_bits=200, heuristic=hm)
+    assert (tr.verdict.fallback, tr.verdict.reason, tr.verdict.esc, tr.verdict.infnan) == (1, oz.REASON_HEURISTIC, -1, 0)
