@@ -19,19 +19,20 @@ namespace oz {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-constexpr int kDM = 128, kDN = 128, kDK = 16;
-constexpr int kDPad = 2;                        // doubles of padding per LDS row (see the bank note below)
-constexpr int kDLd = kDM + kDPad;
+constexpr int kDK = 16;
+constexpr int kDPad = 2;                        // doubles of padding per LDS row (see the bank note above)
+// The tile is T x T with T = 128 (the fast path) or T = 64 (outputs too small to give 128-tiles to
+// every CU).  Per thread and operand a K step has T/16 elements; a wave owns (T/2) x (T/2).
 
 // tile loader: 16 (k) x 128 (r) elements of an operand whose element (r, l) is at
 // base[r*stride_r + l*stride_l]; out-of-range elements are zero.  8 values per thread.
-template <bool ROWS_CONTIG>
-__device__ __forceinline__ void dg_load(double (&v)[8], const double* __restrict__ X, int64_t stride_r,
+template <bool ROWS_CONTIG, int T>
+__device__ __forceinline__ void dg_load(double (&v)[T / 16], const double* __restrict__ X, int64_t stride_r,
                                         int64_t stride_l, int64_t r0, int64_t rows, int64_t l0, int64_t k) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < T / 16; ++q) {
         int rr, ll;
-        if (ROWS_CONTIG) { rr = threadIdx.x & 127; ll = (threadIdx.x >> 7) + 2 * q; }
+        if (ROWS_CONTIG) { rr = threadIdx.x & (T - 1); ll = threadIdx.x / T + (256 / T) * q; }
         else { ll = threadIdx.x & 15; rr = (threadIdx.x >> 4) + 16 * q; }
         const int64_t r = r0 + rr, l = l0 + ll;
         // clamped address + select: the load is unconditional, so the loop stays branch-free
@@ -44,29 +45,34 @@ __device__ __forceinline__ void dg_load(double (&v)[8], const double* __restrict
 // `vo` this thread's byte offset inside it (fixed for the whole kernel), the eight elements of a
 // thread are qstep elements apart.  Uniform base + 32-bit lane offset keeps the addresses in
 // scalar registers.
-__device__ __forceinline__ void dg_load_interior(double (&v)[8], const double* __restrict__ u, uint32_t vo,
+template <int T>
+__device__ __forceinline__ void dg_load_interior(double (&v)[T / 16], const double* __restrict__ u, uint32_t vo,
                                                  int64_t qstep) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int q = 0; q < T / 16; ++q)
         v[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(u + q * qstep) + vo);
 }
 
-template <bool ROWS_CONTIG>
-__device__ __forceinline__ void dg_store(const double (&v)[8], double* lds) {
+template <bool ROWS_CONTIG, int T>
+__device__ __forceinline__ void dg_store(const double (&v)[T / 16], double* lds) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < T / 16; ++q) {
         int rr, ll;
-        if (ROWS_CONTIG) { rr = threadIdx.x & 127; ll = (threadIdx.x >> 7) + 2 * q; }
+        if (ROWS_CONTIG) { rr = threadIdx.x & (T - 1); ll = threadIdx.x / T + (256 / T) * q; }
         else { ll = threadIdx.x & 15; rr = (threadIdx.x >> 4) + 16 * q; }
-        lds[ll * kDLd + rr] = v[q];
+        lds[ll * (T + kDPad) + rr] = v[q];
     }
 }
 
-template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, bool EDGE>
+template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, bool EDGE, int T>
 __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     const Record* rec, int64_t m, int64_t n, int64_t k, double alpha, const double* __restrict__ A,
     int64_t a_sr, int64_t a_sl, const double* __restrict__ B, int64_t b_sr, int64_t b_sl, double beta,
     double* __restrict__ C, int64_t ldc, int ntm, int ntn) {
+    constexpr int kDLd = T + kDPad;      // LDS row length
+    constexpr int WT = T / 2;            // wave tile
+    constexpr int MT = WT / 16;          // MFMA tiles per wave and direction
+    constexpr int EPT = T / 16;          // elements per thread, operand and K step
     __shared__ double At[2][kDK * kDLd];
     __shared__ double Bt[2][kDK * kDLd];
     if (rec && !rec->res.fallback) return;
@@ -87,48 +93,48 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         ti = in_panel / w;
         tj = panel * GW + in_panel % w;
     }
-    const int64_t i0 = int64_t(ti) * kDM, j0 = int64_t(tj) * kDN;
+    const int64_t i0 = int64_t(ti) * T, j0 = int64_t(tj) * T;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wi = wave & 1, wj = wave >> 1;
 
-    v4d acc[4][4];   // [fj][fi]
+    v4d acc[MT][MT];   // [fj][fi]
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
+        for (int b = 0; b < MT; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
 
-    double va[8], vb[8];
+    double va[EPT], vb[EPT];
     // EDGE == false: m, n multiples of the tile and k a multiple of the K step
     const double* ua = A + i0 * a_sr;   // wave-uniform: start of this tile's rows at k = 0
     const double* ub = B + j0 * b_sr;
-    const uint32_t voa = uint32_t(A_ROWS_CONTIG ? (threadIdx.x & 127) * a_sr + (threadIdx.x >> 7) * a_sl
+    const uint32_t voa = uint32_t(A_ROWS_CONTIG ? (threadIdx.x & (T - 1)) * a_sr + (threadIdx.x / T) * a_sl
                                                 : (threadIdx.x >> 4) * a_sr + (threadIdx.x & 15) * a_sl) * 8u;
-    const uint32_t vob = uint32_t(B_ROWS_CONTIG ? (threadIdx.x & 127) * b_sr + (threadIdx.x >> 7) * b_sl
+    const uint32_t vob = uint32_t(B_ROWS_CONTIG ? (threadIdx.x & (T - 1)) * b_sr + (threadIdx.x / T) * b_sl
                                                 : (threadIdx.x >> 4) * b_sr + (threadIdx.x & 15) * b_sl) * 8u;
-    const int64_t qa = A_ROWS_CONTIG ? 2 * a_sl : 16 * a_sr, qb = B_ROWS_CONTIG ? 2 * b_sl : 16 * b_sr;
+    const int64_t qa = A_ROWS_CONTIG ? (256 / T) * a_sl : 16 * a_sr, qb = B_ROWS_CONTIG ? (256 / T) * b_sl : 16 * b_sr;
     if (EDGE) {
-        dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, 0, k);
-        dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, 0, k);
+        dg_load<A_ROWS_CONTIG, T>(va, A, a_sr, a_sl, i0, m, 0, k);
+        dg_load<B_ROWS_CONTIG, T>(vb, B, b_sr, b_sl, j0, n, 0, k);
     } else {
-        dg_load_interior(va, ua, voa, qa);
-        dg_load_interior(vb, ub, vob, qb);
+        dg_load_interior<T>(va, ua, voa, qa);
+        dg_load_interior<T>(vb, ub, vob, qb);
     }
-    dg_store<A_ROWS_CONTIG>(va, At[0]);
-    dg_store<B_ROWS_CONTIG>(vb, Bt[0]);
+    dg_store<A_ROWS_CONTIG, T>(va, At[0]);
+    dg_store<B_ROWS_CONTIG, T>(vb, Bt[0]);
     __syncthreads();
 
     // fragments of MFMA step kk of the K step in LDS buffer `b`: lane group g = lane/16 multiplies
     // k = kk + 8*(g&1) + 4*(g>>1) (see the bank note at the top)
     const int g = lane >> 4;
     const int krow = (8 * (g & 1) + 4 * (g >> 1)) * kDLd;
-    const int la_off = wi * 64 + (lane & 15) + krow, lb_off = wj * 64 + (lane & 15) + krow;
+    const int la_off = wi * WT + (lane & 15) + krow, lb_off = wj * WT + (lane & 15) + krow;
 #define OZ_DG_READ(fa, fb, b, kk)                                                              \
-    _Pragma("unroll") for (int f = 0; f < 4; ++f) {                                            \
+    _Pragma("unroll") for (int f = 0; f < MT; ++f) {                                           \
         fa[f] = At[b][la_off + (kk) * kDLd + f * 16];                                          \
         fb[f] = Bt[b][lb_off + (kk) * kDLd + f * 16];                                          \
     }
 #define OZ_DG_MFMA(fa, fb)                                                                     \
-    _Pragma("unroll") for (int fj = 0; fj < 4; ++fj) _Pragma("unroll") for (int fi = 0; fi < 4; ++fi) \
+    _Pragma("unroll") for (int fj = 0; fj < MT; ++fj) _Pragma("unroll") for (int fi = 0; fi < MT; ++fi) \
         acc[fj][fi] = __builtin_amdgcn_mfma_f64_16x16x4f64(fb[fj], fa[fi], acc[fj][fi], 0, 0, 0);
 
     // Software pipeline of one K step (16 k = 4 MFMA steps of 16 MFMAs), arranged so that the matrix
@@ -140,21 +146,21 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     //   step 2: one LDS store of the next tile per MFMA            (fragments of step 3 are read first)
     //   barrier: next tile visible, nobody reads this buffer any more (step 3 is in registers)
     //   step 3: MFMAs; they cover the barrier and the first fragment read of the next tile
-    double xa[4], xb[4], ya[4], yb[4];
+    double xa[MT], xb[MT], ya[MT], yb[MT];
     int buf = 0;
     OZ_DG_READ(xa, xb, 0, 0);
     for (int64_t l0 = 0; l0 < k; l0 += kDK) {
         const bool have_next = l0 + kDK < k;
         if (EDGE) {
             if (have_next) {
-                dg_load<A_ROWS_CONTIG>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
-                dg_load<B_ROWS_CONTIG>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
+                dg_load<A_ROWS_CONTIG, T>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
+                dg_load<B_ROWS_CONTIG, T>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
             }
         } else {
             ua += have_next ? kDK * a_sl : 0;
             ub += have_next ? kDK * b_sl : 0;
-            dg_load_interior(va, ua, voa, qa);
-            dg_load_interior(vb, ub, vob, qb);
+            dg_load_interior<T>(va, ua, voa, qa);
+            dg_load_interior<T>(vb, ub, vob, qb);
         }
         OZ_DG_READ(ya, yb, buf, 1);
         OZ_DG_MFMA(xa, xb);
@@ -162,11 +168,11 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         OZ_DG_MFMA(ya, yb);
         OZ_DG_READ(ya, yb, buf, 3);
         if (!EDGE || have_next) {
-            dg_store<A_ROWS_CONTIG>(va, At[buf ^ 1]);
-            dg_store<B_ROWS_CONTIG>(vb, Bt[buf ^ 1]);
+            dg_store<A_ROWS_CONTIG, T>(va, At[buf ^ 1]);
+            dg_store<B_ROWS_CONTIG, T>(vb, Bt[buf ^ 1]);
         }
         OZ_DG_MFMA(xa, xb);
-        if (!EDGE) {
+        if (!EDGE && T == 128) {
             // masks: 0x008 MFMA, 0x020 global load, 0x100 LDS read, 0x200 LDS write
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
@@ -187,7 +193,7 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         buf ^= 1;
         if (!EDGE || have_next) { OZ_DG_READ(xa, xb, buf, 0); }
         OZ_DG_MFMA(ya, yb);
-        if (!EDGE) {
+        if (!EDGE && T == 128) {
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
         }
@@ -197,13 +203,13 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
 
     // result register r of tile (fj, fi): j = fj*16 + 4*r + lane/16, i = fi*16 + lane%16
 #pragma unroll
-    for (int fj = 0; fj < 4; ++fj)
+    for (int fj = 0; fj < MT; ++fj)
 #pragma unroll
-        for (int fi = 0; fi < 4; ++fi)
+        for (int fi = 0; fi < MT; ++fi)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int64_t j = j0 + wj * 64 + fj * 16 + 4 * r + (lane >> 4);
-                const int64_t i = i0 + wi * 64 + fi * 16 + (lane & 15);
+                const int64_t j = j0 + wj * WT + fj * 16 + 4 * r + (lane >> 4);
+                const int64_t i = i0 + wi * WT + fi * 16 + (lane & 15);
                 if (!EDGE || (i < m && j < n)) {
                     double out = __dmul_rn(alpha, acc[fj][fi][r]);
                     if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
@@ -219,21 +225,32 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
     // op(B)(l,j): N -> B[l + j*ldb] (k contiguous),    T -> B[j + l*ldb] (rows contiguous)
     const int64_t a_sr = ta ? lda : 1, a_sl = ta ? 1 : lda;
     const int64_t b_sr = tb ? 1 : ldb, b_sl = tb ? ldb : 1;
-    const int ntm = int((m + kDM - 1) / kDM), ntn = int((n + kDN - 1) / kDN);
-    const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
     const bool ac = !ta, bc = tb;
-    const bool edge = (m % kDM) || (n % kDN) || (k % kDK);
+    // 64 x 64 tiles when 128 x 128 tiles would leave more than half of the 2 x 256 workgroup slots empty
+    const int64_t tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
+    int device = 0, num_cu = 256;
+    if (hipGetDevice(&device) == hipSuccess) (void)hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, device);
+    const bool small = tiles128 < num_cu;
+    const int T = small ? 64 : 128;
+    const int ntm = int((m + T - 1) / T), ntn = int((n + T - 1) / T);
+    const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
+    const bool edge = (m % T) || (n % T) || (k % kDK);
+#define OZ_DG_T(AC, BC, TT)                                                                                    \
+    {                                                                                                          \
+        if (edge) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, true, TT>), grid, block, 0, st, rec, m, n, k,   \
+                                     alpha, A, a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);             \
+        else hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, false, TT>), grid, block, 0, st, rec, m, n, k,       \
+                                alpha, A, a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);                  \
+    }
 #define OZ_DG(AC, BC)                                                                                          \
     {                                                                                                          \
-        if (edge) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, true>), grid, block, 0, st, rec, m, n, k, alpha, A, \
-                                     a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);                       \
-        else hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, false>), grid, block, 0, st, rec, m, n, k, alpha, A, \
-                                a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);                            \
+        if (small) OZ_DG_T(AC, BC, 64) else OZ_DG_T(AC, BC, 128)                                               \
     }
     if (ac && bc) OZ_DG(true, true)
     else if (ac && !bc) OZ_DG(true, false)
     else if (!ac && bc) OZ_DG(false, true)
     else OZ_DG(false, false)
+#undef OZ_DG_T
 #undef OZ_DG
 }
 

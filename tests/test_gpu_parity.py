@@ -335,7 +335,8 @@ def test_heuristic_after_the_esc(lib):
     assert (v.fallback, v.reason) == (1, oz.REASON_HEURISTIC)
 
 
-@pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512)])   # ragged path, interior fast path
+# 64-tiles: ragged and interior; 128-tiles (at least 256 of them): ragged and interior
+@pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512), (2100, 2050, 50), (2048, 2048, 64)])
 @pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
 def test_native_fp64_gemm(lib, ta, tb, shape):
     g, h = lib
@@ -343,7 +344,8 @@ def test_native_fp64_gemm(lib, ta, tb, shape):
     A, B, Cin = wl.lognormal_spread(m, k, n, 0.5, seed=40, with_c=True)
     got, _, res = run_gpu(g, h, A, B, 1.5, 0.5, Cin, ta, tb, pad=2 if m % 128 else 0, mode=g.OZ_NATIVE)
     assert (res.fallback, res.reason) == (1, oz.REASON_NATIVE)
-    idx = [(i, j) for i in range(0, m, 13) for j in range(0, n, 11)]
+    idx = [(i, j) for i in range(0, m, 13 if m < 1000 else 131) for j in range(0, n, 11 if n < 1000 else 127)]
+    idx += [(m - 1, n - 1), (0, n - 1), (m - 1, 0)]
     exact = ex.exact_entries(A, B, idx, 1.5, 0.5, Cin)
     den = ex.bound_denominator(A, B, idx, 1.5, 0.5, Cin)
     assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
