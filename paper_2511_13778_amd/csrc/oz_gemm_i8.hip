@@ -69,25 +69,29 @@ __device__ __forceinline__ v4i as_v4i(const uint4& v) { return v4i{int(v.x), int
 // linear workgroup id -> tile coordinates.  Ids are dealt round-robin to the 8 XCDs by the
 // hardware; each XCD is given a contiguous range of a tile order in which 32 consecutive tiles
 // form a 4 (i) x 8 (j) block.
-// With a k split (zsplit > 1) a work unit is (tile, part of the k range); units are ordered part by
-// part, so the units an XCD runs together still are neighbouring tiles of the same k range.
-__device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int zsplit, int& ti, int& tj, int& z,
-                                        int& xcd, int& slot, int& xcd_tiles) {
-    const int tiles = nti * ntj;
-    const int total = tiles * zsplit;
-    xcd = bid & 7;
-    slot = bid >> 3;
-    const int per = total >> 3, rem = total & 7;
-    xcd_tiles = per + (xcd < rem ? 1 : 0);
-    const int unit = xcd * per + min(xcd, rem) + slot;
-    z = unit / tiles;
-    const int lin = unit - z * tiles;
+// position `lin` of the tile order -> tile coordinates: panels of 8 tile columns, i fastest inside
+__device__ __forceinline__ void lin_to_tile(int lin, int nti, int ntj, int& ti, int& tj) {
     constexpr int GW = 8;
     const int panel = lin / (GW * nti);
     const int in_panel = lin - panel * GW * nti;
     const int w = min(GW, ntj - panel * GW);
     ti = in_panel / w;
     tj = panel * GW + in_panel % w;
+}
+
+// A launch covers the tiles [tile_begin, tile_begin + tile_count) of the tile order.  With a k split
+// (zsplit > 1) a work unit is (tile, part of the k range); units are ordered part by part, so the
+// units an XCD runs together still are neighbouring tiles of the same k range.
+__device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int tile_begin, int tile_count, int zsplit,
+                                        int& ti, int& tj, int& z, int& xcd, int& slot, int& xcd_tiles) {
+    const int total = tile_count * zsplit;
+    xcd = bid & 7;
+    slot = bid >> 3;
+    const int per = total >> 3, rem = total & 7;
+    xcd_tiles = per + (xcd < rem ? 1 : 0);
+    const int unit = xcd * per + min(xcd, rem) + slot;
+    z = unit / tile_count;
+    lin_to_tile(tile_begin + unit - z * tile_count, nti, ntj, ti, tj);
 }
 
 // 64 lanes x 16 B from global memory into LDS: lane l's 16 bytes land at lds_addr + LDS_IMM + 16*l.
@@ -106,7 +110,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                                                       const int8_t* __restrict__ Bs,
                                                       int32_t* __restrict__ P, int64_t mp,
                                                       int64_t np, int64_t kp, int s_cap,
-                                                      Record* rec, int full_chip, int zsplit) {
+                                                      Record* rec, int full_chip, int zsplit,
+                                                      int tile_begin, int tile_count) {
     extern __shared__ __align__(16) uint8_t lds[];
     if (rec->res.fallback) return;
     const int S = rec->res.slices_used;
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     const int nkb = int((kp + kblk - 1) / kblk);
 
     int ti, tj, z, xcd, slot, xcd_tiles;
-    tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), zsplit, ti, tj, z, xcd, slot, xcd_tiles);
+    tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), tile_begin, tile_count, zsplit, ti, tj, z, xcd, slot, xcd_tiles);
 
     // This workgroup's share of the K steps: part z of zsplit equal parts of the whole k range (one
     // part = everything when the call has enough tiles to fill the chip).  Parts of the same k-block
@@ -339,37 +344,57 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 #undef OZ_READ_A
 #undef OZ_READ_B
 
-// P = 0 before a launch whose workgroups add their parts of the k range into it
-__global__ __launch_bounds__(256) void zero_planes_kernel(int4* __restrict__ P, size_t n16, const Record* rec) {
+// P = 0 on the tiles of a launch whose workgroups add their parts of the k range into it.
+// grid (tiles of the launch, planes); a workgroup clears one 256 x 256 block of one plane.
+__global__ __launch_bounds__(256) void zero_tiles_kernel(int32_t* __restrict__ P, int64_t mp, int64_t np, int nti,
+                                                         int ntj, int tile_begin, const Record* rec) {
     if (rec->res.fallback) return;
-    const size_t t = size_t(blockIdx.x) * 256 + threadIdx.x;
-    if (t < n16) P[t] = make_int4(0, 0, 0, 0);
+    int ti, tj;
+    lin_to_tile(tile_begin + int(blockIdx.x), nti, ntj, ti, tj);
+    int32_t* base = P + (int64_t(blockIdx.y) * np + int64_t(tj) * kBN) * mp + int64_t(ti) * kBM;
+    const int col = threadIdx.x & 63, row0 = threadIdx.x >> 6;   // 64 int4 per row of the block
+    for (int jj = row0; jj < kBN; jj += 4)
+        reinterpret_cast<int4*>(base + int64_t(jj) * mp)[col] = make_int4(0, 0, 0, 0);
 }
 
 void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p) {
     // the attribute is per device and cheap to set; no process-wide cache that a second device would miss
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-    const unsigned tiles = unsigned((p.mp / kBM) * (p.np / kBN));
-    // Too few tiles to fill the chip: split the k range so that about one workgroup per CU results,
-    // each part keeping at least kMinSplitSteps K steps.  The parts add into P with integer atomics.
+    const int nti = int(p.mp / kBM), ntj = int(p.np / kBN);
+    const int tiles = nti * ntj;
     const int64_t kt_total = p.kp / kBK;
-    int zsplit = 1;
-    if (tiles * 4 <= unsigned(p.num_cu) * 3) {
-        zsplit = int(p.num_cu / tiles);
-        if (zsplit > kt_total / kMinSplitSteps) zsplit = int(kt_total / kMinSplitSteps);
-        if (zsplit < 1) zsplit = 1;
-    }
-    if (zsplit > 1) {
-        const size_t words = size_t(p.nkb) * p.s_cap * p.np * p.mp;
-        hipLaunchKernelGGL(zero_planes_kernel, dim3(unsigned((words / 4 + 255) / 256)), dim3(256), 0, st,
-                           reinterpret_cast<int4*>(w.P), words / 4, w.rec);
-    }
+    const int planes = p.nkb * p.s_cap;
     // the workgroup-to-XCD reasoning behind the in-step waits holds for the whole chip only
     // (8 XCDs of 32 CUs); a partitioned device runs the same kernel without them
     const int full_chip = p.num_cu == 8 * kRoundTiles ? 1 : 0;
-    hipLaunchKernelGGL(gemm_i8_kernel, dim3(tiles * unsigned(zsplit)), dim3(256), kGemmLds, st, w.As, w.Bs, w.P,
-                       p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, zsplit);
+    // k split for `count` tiles that cannot fill the chip: about one workgroup per CU, each part
+    // keeping at least kMinSplitSteps K steps; the parts add into P with integer atomics
+    auto split_for = [&](int count) -> int {
+        int zs = p.num_cu / count;
+        if (zs > kt_total / kMinSplitSteps) zs = int(kt_total / kMinSplitSteps);
+        return zs < 1 ? 1 : zs;
+    };
+    auto launch = [&](int begin, int count, int zs) {
+        if (zs > 1)
+            hipLaunchKernelGGL(zero_tiles_kernel, dim3(unsigned(count), unsigned(planes)), dim3(256), 0, st, w.P,
+                               p.mp, p.np, nti, ntj, begin, w.rec);
+        hipLaunchKernelGGL(gemm_i8_kernel, dim3(unsigned(count) * unsigned(zs)), dim3(256), kGemmLds, st, w.As,
+                           w.Bs, w.P, p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, zs, begin, count);
+    };
+    // Tiles are dealt in rounds of one per CU.  A call with less than three quarters of a round is
+    // split along k as a whole; otherwise the full rounds run unsplit and a last round that would
+    // be less than three quarters full is split along k in a launch of its own.
+    const int round = p.num_cu;
+    const int full = tiles / round * round, rest = tiles - full;
+    if (full == 0) {
+        launch(0, tiles, rest * 4 <= round * 3 ? split_for(tiles) : 1);
+    } else if (rest == 0 || rest * 4 > round * 3 || split_for(rest) == 1) {
+        launch(0, tiles, 1);
+    } else {
+        launch(0, full, 1);
+        launch(full, rest, split_for(rest));
+    }
 }
 
 }  // namespace oz
