@@ -351,6 +351,29 @@ def test_native_fp64_gemm(lib, ta, tb, shape):
     assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_randomized_configurations(lib, seed):
+    # shapes, modes, transposes, scalars, leading dimensions, exponent spreads and block lengths drawn
+    # from a seeded generator; everything the oracle defines must match bit for bit
+    g, h = lib
+    rng = np.random.default_rng(1000 + seed)
+    m, n, k = int(rng.integers(1, 260)), int(rng.integers(1, 300)), int(rng.integers(1, 500))
+    phi = float(rng.choice([0.0, 0.3, 1.0, 2.0]))
+    A, B, Cin = wl.lognormal_spread(m, k, n, phi, seed=2000 + seed, with_c=True)
+    if rng.random() < 0.3:                               # sprinkle zeros, a zero row and a zero column
+        A[rng.random(A.shape) < 0.05] = 0.0
+        A[int(rng.integers(m)), :] = 0.0
+        B[:, int(rng.integers(n))] = 0.0
+    mode = str(rng.choice(["dynamic", "forced", "fixed_guarded", "unguarded"]))
+    alpha = float(rng.choice([1.0, -1.0, 0.75, 3.0]))
+    beta = float(rng.choice([0.0, 1.0, -0.5]))
+    ta, tb = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+    max_bits = 200 if mode == "dynamic" else int(rng.choice([39, 55, 63]))
+    check_against_oracle(g, h, A, B, alpha, beta, Cin if beta != 0.0 else None, mode=mode, max_bits=max_bits,
+                         esc_block=int(rng.choice([0, 16, 32, 128])), transa=ta, transb=tb,
+                         pad=int(rng.integers(0, 4)), bound=(mode == "dynamic"))
+
+
 def test_argument_errors(lib):
     g, h = lib
     opts = g.make_opts(mode=g.OZ_FORCED_GUARDED, max_bits=55)
