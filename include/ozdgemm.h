@@ -113,6 +113,22 @@ oz_status_t oz_dgemm(oz_handle_t handle, void* stream, char transa, char transb,
                      const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
                      oz_result_t* result);
 
+/* batch_count independent problems of one shape: problem b uses A + b*stride_a, B + b*stride_b,
+ * C + b*stride_c (strides in elements; 0 repeats an operand; the C blocks must not overlap) and
+ * writes its own record to results[b] (device array of batch_count records, may be NULL).  Every
+ * problem goes through the whole decision process on its own, so slice counts and fallbacks may
+ * differ inside a batch (the paper's application runs show a distribution of slice counts over
+ * the GEMMs of one factorisation: section "Application-Level Integration").  The problems run
+ * one after the other on `stream` and share `workspace`, which is sized as for one oz_dgemm call.
+ * batch_count == 0 is a no-op; errors are those of oz_dgemm, checked before anything is enqueued. */
+oz_status_t oz_dgemm_strided_batched(oz_handle_t handle, void* stream, char transa, char transb,
+                                     int64_t m, int64_t n, int64_t k, double alpha,
+                                     const double* A, int64_t lda, int64_t stride_a,
+                                     const double* B, int64_t ldb, int64_t stride_b,
+                                     double beta, double* C, int64_t ldc, int64_t stride_c,
+                                     int64_t batch_count, const oz_opts_t* opts,
+                                     void* workspace, size_t workspace_bytes, oz_result_t* results);
+
 /* Layout of the intermediate buffers inside the workspace after an oz_dgemm call, for
  * inspection by tests (all offsets in bytes from `workspace`):
  *   eA   int32[mp]              row exponents of op(A); -12288 marks an all-zero row

@@ -342,4 +342,27 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
     return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
 }
 
+oz_status_t oz_dgemm_strided_batched(oz_handle_t h, void* stream, char transa, char transb, int64_t m,
+                                     int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
+                                     int64_t stride_a, const double* B, int64_t ldb, int64_t stride_b,
+                                     double beta, double* C, int64_t ldc, int64_t stride_c,
+                                     int64_t batch_count, const oz_opts_t* opts, void* workspace,
+                                     size_t workspace_bytes, oz_result_t* results) {
+    if (batch_count < 0 || stride_a < 0 || stride_b < 0 || stride_c < 0) return OZ_ERR_ARG;
+    if (batch_count > 1 && m > 0 && n > 0 && stride_c < ldc * (n - 1) + m) return OZ_ERR_ARG;   // C blocks overlap
+    // validate everything once, before the first problem is enqueued
+    bool ta, tb;
+    if (!h || !opts || !parse_trans(transa, ta) || !parse_trans(transb, tb) || !valid_opts(*opts)) return OZ_ERR_ARG;
+    if (!check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
+    if (batch_count > 0 && oz_dgemm_workspace_bytes(h, transa, transb, m, n, k, opts) > workspace_bytes)
+        return OZ_ERR_WORKSPACE;
+    for (int64_t b = 0; b < batch_count; ++b) {
+        const oz_status_t st = oz_dgemm(h, stream, transa, transb, m, n, k, alpha, A ? A + b * stride_a : A, lda,
+                                        B ? B + b * stride_b : B, ldb, beta, C ? C + b * stride_c : C, ldc, opts,
+                                        workspace, workspace_bytes, results ? results + b : nullptr);
+        if (st != OZ_OK) return st;
+    }
+    return OZ_OK;
+}
+
 }  // extern "C"

@@ -42,7 +42,7 @@ class oz_layout_t(C.Structure):
 
 
 EXPORTS = ("oz_create", "oz_destroy", "oz_default_opts", "oz_set_heuristic",
-           "oz_dgemm_workspace_bytes", "oz_dgemm", "oz_dgemm_layout", "oz_profile_enable",
+           "oz_dgemm_workspace_bytes", "oz_dgemm", "oz_dgemm_strided_batched", "oz_dgemm_layout", "oz_profile_enable",
            "oz_profile_read", "oz_native_dgemm", "oz_status_string")
 
 _lib = None
@@ -81,6 +81,10 @@ def load_library() -> C.CDLL:
     lib.oz_dgemm.argtypes = [H, C.c_void_p] + dims + gemm_args + [C.POINTER(oz_opts_t), C.c_void_p,
                                                                     C.c_size_t, C.c_void_p]
     lib.oz_dgemm.restype = C.c_int
+    lib.oz_dgemm_strided_batched.argtypes = [H, C.c_void_p] + dims + [
+        C.c_double, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_double, C.c_void_p,
+        C.c_int64, C.c_int64, C.c_int64, C.POINTER(oz_opts_t), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.oz_dgemm_strided_batched.restype = C.c_int
     lib.oz_native_dgemm.argtypes = [H, C.c_void_p] + dims + gemm_args
     lib.oz_native_dgemm.restype = C.c_int
     lib.oz_profile_enable.argtypes = [H, C.c_int32]
@@ -157,6 +161,14 @@ class Handle:
         _check(self.lib.oz_dgemm(self._h, stream_ptr, transa.encode(), transb.encode(), m, n, k, alpha,
                                  A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc, C.byref(opts), ws_ptr, ws_bytes,
                                  result_ptr), "oz_dgemm")
+
+    def dgemm_strided_batched(self, stream_ptr, transa, transb, m, n, k, alpha, A_ptr, lda, stride_a, B_ptr, ldb,
+                              stride_b, beta, C_ptr, ldc, stride_c, batch_count, opts: oz_opts_t, ws_ptr, ws_bytes,
+                              results_ptr=None):
+        _check(self.lib.oz_dgemm_strided_batched(self._h, stream_ptr, transa.encode(), transb.encode(), m, n, k,
+                                                 alpha, A_ptr, lda, stride_a, B_ptr, ldb, stride_b, beta, C_ptr,
+                                                 ldc, stride_c, batch_count, C.byref(opts), ws_ptr, ws_bytes,
+                                                 results_ptr), "oz_dgemm_strided_batched")
 
     def native_dgemm(self, stream_ptr, transa, transb, m, n, k, alpha, A_ptr, lda, B_ptr, ldb, beta, C_ptr,
                      ldc):

@@ -374,6 +374,45 @@ def test_randomized_configurations(lib, seed):
                          pad=int(rng.integers(0, 4)), bound=(mode == "dynamic"))
 
 
+def test_strided_batched(lib):
+    # four problems of one shape in one call: each takes its own decision (slice counts differ, one
+    # falls back on a NaN), results and records per problem as from separate oz_dgemm calls
+    g, h = lib
+    m, n, k, nb = 150, 120, 300, 4
+    As, Bs, Cs = [], [], []
+    for b, phi in enumerate([0.0, 2.0, 0.5, 1.0]):
+        A, B, Cin = wl.lognormal_spread(m, k, n, phi, seed=60 + b, with_c=True)
+        As.append(A); Bs.append(B); Cs.append(Cin)
+    As[2][7, 11] = np.nan
+    opts = g.make_opts(mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200, heuristic=0)
+    ws_bytes = h.workspace_bytes("N", "N", m, n, k, opts)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    dA = torch.from_numpy(np.stack([a.T.copy() for a in As])).cuda()     # (nb, k, m): column-major m x k each
+    dB = torch.from_numpy(np.stack([b_.T.copy() for b_ in Bs])).cuda()
+    dC = torch.from_numpy(np.stack([c.T.copy() for c in Cs])).cuda()
+    recs = torch.zeros((nb, 6), dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    h.dgemm_strided_batched(st, "N", "N", m, n, k, -1.0, dA.data_ptr(), m, m * k, dB.data_ptr(), k, k * n, 0.5,
+                            dC.data_ptr(), m, m * n, nb, opts, ws.data_ptr(), ws_bytes, recs.data_ptr())
+    torch.cuda.synchronize()
+    got, recs = dC.cpu().numpy(), recs.cpu().numpy()
+    seen = set()
+    for b in range(nb):
+        tr = oz.emulated_dgemm(As[b], Bs[b], -1.0, 0.5, Cs[b], mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200)
+        v = tr.verdict
+        assert tuple(int(x) for x in recs[b]) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan)
+        if v.fallback:
+            assert np.isnan(got[b].T[7, :]).all()
+        else:
+            np.testing.assert_array_equal(got[b].T, tr.C)
+            seen.add(v.slices_used)
+    assert recs[2][0] == 1 and recs[2][1] == oz.REASON_INFNAN and len(seen) >= 2
+    # overlapping C blocks are refused before anything runs
+    with pytest.raises(g.OzError):
+        h.dgemm_strided_batched(st, "N", "N", m, n, k, 1.0, dA.data_ptr(), m, m * k, dB.data_ptr(), k, k * n, 0.0,
+                                dC.data_ptr(), m, m * n - 1, nb, opts, ws.data_ptr(), ws_bytes, None)
+
+
 def test_argument_errors(lib):
     g, h = lib
     opts = g.make_opts(mode=g.OZ_FORCED_GUARDED, max_bits=55)
