@@ -46,22 +46,28 @@ static_assert(kKPad % kBK == 0, "k padding must cover whole K steps");
 static_assert(kDmaPerStage == 8, "the vmcnt immediates below assume 8 DMA instructions per stage");
 
 constexpr int kRoundTiles = 32;       // workgroups an XCD runs at a time: 32 CUs, one workgroup each
-constexpr int kMaxSyncSpins = 8192;   // upper bound of the wait for the other workgroups of a round
+constexpr int kMaxSyncSpins = 384;    // upper bound of the wait for the other workgroups of a round
 constexpr int kMidSyncMinK = 12288;
 constexpr int kMinSplitSteps = 8;     // a part of a split k range keeps at least this many K steps   // from this k on, workgroups also wait after every anti-diagonal
 
-// Waits (bounded) until `target` workgroups have arrived at *counter.  The wait only improves cache
-// locality: correctness does not depend on it, and every wave gets past it whatever the other
-// workgroups do.
-__device__ __forceinline__ void round_sync(int32_t* counter, int target) {
+// Records this workgroup's arrival at *counter and, if `wait`, waits (bounded, about half a
+// millisecond) until `target` workgroups have arrived.  The wait only improves cache locality:
+// correctness does not depend on it, and every wave gets past it whatever the other workgroups do.
+// Returns whether the others were met in time; a workgroup that was not (the chip is shared with
+// another kernel, or workgroups are not placed as assumed) keeps counting its arrivals, which the
+// others rely on, but stops waiting, so the cost of a wrong assumption is paid once per tile.
+__device__ __forceinline__ bool round_sync(int32_t* counter, int target, bool wait) {
+    int met = 0;
     if (threadIdx.x == 0) {
         atomicAdd(counter, 1);
-        for (int spin = 0; spin < kMaxSyncSpins; ++spin) {
-            if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
-            __builtin_amdgcn_s_sleep(8);
+        if (wait) {
+            for (int spin = 0; spin < kMaxSyncSpins && !met; ++spin) {
+                met = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target;
+                if (!met) __builtin_amdgcn_s_sleep(8);
+            }
         }
     }
-    __syncthreads();
+    return __syncthreads_or(met) != 0;
 }
 
 __device__ __forceinline__ v4i as_v4i(const uint4& v) { return v4i{int(v.x), int(v.y), int(v.z), int(v.w)}; }
@@ -146,7 +152,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     const int sync_base = sync_round * kRoundTiles * sync_steps;
     const bool sync_on = full_chip && xcd_tiles > kRoundTiles && sync_members > 1;
     int sync_q = 0;
-    if (sync_on) round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members);
+    bool sync_wait = true;
+    if (sync_on) sync_wait = round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members, sync_wait);
 
     const int64_t i0 = int64_t(ti) * kBM, j0 = int64_t(tj) * kBN;
 
@@ -328,7 +335,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                     }
                     acc[fj][fi] = zero;
                 }
-            if (sync_on && sync_q < sync_steps) round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members);
+            if (sync_on && sync_q < sync_steps)
+                sync_wait = round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members, sync_wait);
         }
     }
     // drain the surplus transfers before the workgroup's LDS is released
