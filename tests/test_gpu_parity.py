@@ -413,6 +413,38 @@ def test_strided_batched(lib):
                                 dC.data_ptr(), m, m * n - 1, nb, opts, ws.data_ptr(), ws_bytes, None)
 
 
+def test_call_can_be_captured_in_a_graph(lib):
+    # the call only enqueues kernels (no allocation, no memset, no synchronisation), so it can be
+    # captured; every replay must reproduce the eager result, with eager calls between the replays
+    g, h = lib
+    n = 300
+    A, B = wl.lognormal_spread(n, n, n, 1.0, seed=70)
+    dA, dB = g.to_colmajor(A), g.to_colmajor(B)
+    dC = torch.zeros((n, n), dtype=torch.float64, device="cuda")
+    gm = g.Gemm(h, n, n, n, g.make_opts(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0))
+    gm.run(dA, n, dB, n, dC, n)
+    torch.cuda.synchronize()
+    ref = dC.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gm.run(dA, n, dB, n, dC, n)                   # warm-up on a side stream, as capture requires
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gm.run(dA, n, dB, n, dC, n)
+    for _ in range(3):
+        dC.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dC, ref)
+        gm.run(dA, n, dB, n, dC, n)
+        torch.cuda.synchronize()
+        assert torch.equal(dC, ref)
+    assert gm.result().fallback == 0
+
+
 def test_argument_errors(lib):
     g, h = lib
     opts = g.make_opts(mode=g.OZ_FORCED_GUARDED, max_bits=55)
