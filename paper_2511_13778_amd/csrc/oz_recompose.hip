@@ -32,12 +32,14 @@ __global__ __launch_bounds__(256) void recompose_kernel(const int32_t* __restric
     if (i0 >= m) return;
     const int eb = eB[j];
     const int64_t plane = np * mp;
-    const int4* p = reinterpret_cast<const int4*>(P + j * mp + i0);   // mp and i0 are multiples of 4
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const i32x4* p = reinterpret_cast<const i32x4*>(P + j * mp + i0);   // mp and i0 are multiples of 4
     double R[4] = {0.0, 0.0, 0.0, 0.0};
     for (int kb = 0; kb < nkb; ++kb) {
         double Rb[4] = {0.0, 0.0, 0.0, 0.0};
         for (int d = S - 1; d >= 0; --d) {
-            const int4 v = p[((int64_t(kb) * s_cap + d) * plane) / 4];
+            // the planes are read once: streaming loads keep them out of the way of C
+            const i32x4 v = __builtin_nontemporal_load(&p[((int64_t(kb) * s_cap + d) * plane) / 4]);
             Rb[0] = double(v.x) + Rb[0] * 0x1p-8;
             Rb[1] = double(v.y) + Rb[1] * 0x1p-8;
             Rb[2] = double(v.z) + Rb[2] * 0x1p-8;
