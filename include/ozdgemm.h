@@ -63,7 +63,10 @@ typedef struct {
                              guarded/dynamic modes: cap on target_bits + ESC.  1..200 */
     int32_t slices;       /* > 0 overrides the slice count of the fixed/forced modes (1..26) */
     int32_t esc_block;    /* block length b of the coarsened ESC; 0 = 64.  Multiple of 16, <= 1024 */
-    int32_t heuristic;    /* OZ_DYNAMIC only: 1 = apply the run-time cost model, 0 = do not */
+    int32_t heuristic;    /* OZ_DYNAMIC only: 1 = apply the run-time cost model, 0 = do not.  The model is
+                             first evaluated on the host for the smallest slice count any input can
+                             get (ESC = 1); if that already loses against FP64 the call runs the
+                             native GEMM without scanning A and B: reason 3, esc -1, infnan 0 */
 } oz_opts_t;
 
 /* Decision record, written to DEVICE memory by the verdict kernel. */
