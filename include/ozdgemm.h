@@ -18,6 +18,7 @@
  *     frees device memory and never synchronises: a call only enqueues kernels on `stream`
  *     (a hipStream_t passed as void*) and returns.
  *   - m == 0 or n == 0: nothing is done.  k == 0 or alpha == 0: C = beta * C.
+ *     Limits: m, n <= 2^22, k <= 2^21 (larger sizes are an argument error).
  *   - Return values report host-side argument errors only.  Numerical conditions (Inf/NaN in
  *     the inputs, exponent span too wide, emulation predicted slower) are never errors: they
  *     select the native FP64 path and are recorded in *result.
@@ -37,7 +38,7 @@ typedef struct oz_handle* oz_handle_t;
 
 typedef enum {
     OZ_OK = 0,
-    OZ_ERR_ARG = 1,        /* bad trans, negative size, leading dimension too small, bad option */
+    OZ_ERR_ARG = 1,        /* bad trans, negative or too large size, leading dimension too small, bad option */
     OZ_ERR_WORKSPACE = 2,  /* workspace NULL, misaligned (256 B) or smaller than required */
     OZ_ERR_DEVICE = 3,     /* device is not gfx950 or cannot be selected */
     OZ_ERR_HIP = 4         /* a HIP runtime call (launch, event) failed */

@@ -67,7 +67,8 @@ int slice_cap(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int6
 
 bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int64_t k, Problem& p) {
     if (m < 0 || n < 0 || k < 0) return false;
-    if (m > (int64_t(1) << 24) || n > (int64_t(1) << 24) || k > (int64_t(1) << 24)) return false;
+    // launch grids carry k/64 and n/128 in a 16-bit dimension
+    if (m > kMaxRows || n > kMaxRows || k > kMaxK) return false;
     p.m = m; p.n = n; p.k = k;
     p.mp = round_up(m > 0 ? m : 1, kRowPad);
     p.np = round_up(n > 0 ? n : 1, kRowPad);

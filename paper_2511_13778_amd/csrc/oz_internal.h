@@ -13,6 +13,8 @@ constexpr int kHeadroomBits = 1;      // spare bit in the leading digit: |X| < 2
 constexpr int kMaxSlices = 26;        // 200 mantissa bits
 constexpr int kEscCap = 4096;         // reported ESC is clamped to this
 constexpr int kDefaultEscBlock = 64;
+constexpr int64_t kMaxRows = int64_t(1) << 22;   // largest m, n
+constexpr int64_t kMaxK = int64_t(1) << 21;      // largest k
 
 // Exponents are kept as int16 in the block tables.  Real exponents lie in [-1074, 1023].
 // kExpZeroInMin: Min of a block that holds a zero (exp(0) = -infinity).

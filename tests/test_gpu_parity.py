@@ -463,4 +463,8 @@ def test_argument_errors(lib):
             call(**kw)
         assert e.value.status == status
     assert h.workspace_bytes("N", "Q", 64, 64, 64, opts) == 0
+    # sizes beyond what the launch grids carry are refused, not launched
+    assert h.workspace_bytes("N", "N", 64, 64, (1 << 21) + 1, opts) == 0
+    assert h.workspace_bytes("N", "N", (1 << 22) + 1, 64, 64, opts) == 0
+    assert h.workspace_bytes("N", "N", 64, 64, 1 << 21, opts) > 0
     torch.cuda.synchronize()
