@@ -40,7 +40,7 @@ typedef enum {
     OZ_OK = 0,
     OZ_ERR_ARG = 1,        /* bad trans, negative or too large size, leading dimension too small, bad option */
     OZ_ERR_WORKSPACE = 2,  /* workspace NULL, misaligned (256 B) or smaller than required */
-    OZ_ERR_DEVICE = 3,     /* device is not gfx950 or cannot be selected */
+    OZ_ERR_DEVICE = 3,     /* device is not gfx950, or the current device is not the handle's */
     OZ_ERR_HIP = 4         /* a HIP runtime call (launch, event) failed */
 } oz_status_t;
 

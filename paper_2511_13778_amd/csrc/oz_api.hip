@@ -123,6 +123,12 @@ Workspace bind(void* base, const Problem& p, const oz_layout_t& L) {
     return w;
 }
 
+// the handle is bound to one device; kernels launch on the current one
+bool on_handle_device(const oz_handle& h) {
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == h.device;
+}
+
 bool check_dims(bool ta, bool tb, int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb, int64_t ldc) {
     const int64_t rows_a = ta ? k : m, rows_b = tb ? n : k;
     if (lda < (rows_a > 1 ? rows_a : 1)) return false;
@@ -260,6 +266,7 @@ oz_status_t oz_native_dgemm(oz_handle_t h, void* stream, char transa, char trans
     if (m < 0 || n < 0 || k < 0 || !check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
     if (m == 0 || n == 0) return OZ_OK;
     if (!C || (k > 0 && alpha != 0.0 && (!A || !B))) return OZ_ERR_ARG;
+    if (!on_handle_device(*h)) return OZ_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (k == 0 || alpha == 0.0) launch_scale_c(st, m, n, beta, C, ldc);
     else launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
@@ -278,6 +285,7 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
     if (!check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
     if (m == 0 || n == 0) return OZ_OK;
     if (!C) return OZ_ERR_ARG;
+    if (!on_handle_device(*h)) return OZ_ERR_DEVICE;
     oz_layout_t L;
     make_layout(p, L);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < L.total_bytes)
