@@ -11,6 +11,9 @@ phi in {0.1, 1, 2}, alpha = 1.5, beta = 0.5, random C:
   slices  fixed slice count swept S = 4..12 without guardrails: time against S(S+1)/2.
   block   block length b of the coarsened ESC swept: reported ESC, slice count a dynamic run would
           take, and the time of the ESC stage.
+  shapes  (--shapes) rectangular problems: the tall-skinny / long-k / short-k shapes with row i of
+          A scaled by 2^(i mod 40), and the two GEMM shapes of a blocked QR trailing update;
+          emulated (forced 55 bits) against both native FP64 GEMMs, and what the heuristic decides.
 
 Writes plain-text tables next to this file (experiments/results/).  Inputs are the seeded
 generators of paper_2511_13778_amd/workloads.py; nothing is read from outside the repository.
@@ -56,8 +59,47 @@ def emulated(torch, g, h, n, dA, dB, dC, reps, **opt):
     return ms, res, dict(zip(g.STAGE_NAMES, stages))
 
 
+SHAPES = [(16384, 16384, 512), (1024, 1024, 65536), (32768, 256, 8192), (4096, 4096, 4096), (2048, 2048, 2048),
+          (256, 8192, 8192), (8192, 8192, 256)]
+
+
+def shapes(torch, g, h, reps):
+    from oracle import ozaki as oz   # host-side cost model only (the same integers the library uses)
+    from paper_2511_13778_amd import workloads as wl
+    st = torch.cuda.current_stream().cuda_stream
+    lines = ["# rectangular problems, row i of A scaled by 2^(i mod 40), alpha = 1, beta = 0; %d timed calls per entry" % reps,
+             "# heuristic: what DYNAMIC mode with the cost model on would do with 7 slices (the fewest a call can get)",
+             "m      n      k      | emulated forced 55: ms TFLOP/s (gemm recompose slicing ms) | own FP64 ms | vendor FP64 ms | x vendor | heuristic"]
+    for m, n, k in SHAPES:
+        print("shape %d %d %d" % (m, n, k), flush=True)
+        A, B, _ = wl.row_scaled(m, k, n, seed=6)
+        dA, dB = g.to_colmajor(A), g.to_colmajor(B)
+        del A, B
+        dC = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+        gm = g.Gemm(h, m, n, k, g.make_opts(mode=g.OZ_FORCED_GUARDED, max_bits=55, heuristic=0))
+        fn = lambda: gm.run(dA, m, dB, k, dC, m, 1.0, 0.0)
+        fn()
+        torch.cuda.synchronize()
+        h.profile_enable(reps)
+        ms = timed(torch, fn, reps)
+        sm = dict(zip(g.STAGE_NAMES, np.array([h.profile_read(c) for c in range(reps)]).mean(axis=0)))
+        t_own = timed(torch, lambda: h.native_dgemm(st, "N", "N", m, n, k, 1.0, dA.data_ptr(), m, dB.data_ptr(), k, 0.0,
+                                                    dC.data_ptr(), m), reps)
+        t_ven = timed(torch, lambda: torch.matmul(dB, dA), reps)
+        slower = oz.HeuristicModel().emulation_slower(7, m, n, k)
+        lines.append("%-6d %-6d %-6d | %8.3f %6.1f (%.3f %.3f %.3f) | %8.3f | %8.3f | %5.2f | %s"
+                     % (m, n, k, ms, 2.0 * m * n * k / ms * 1e-9, sm["slice_gemm_i8"], sm["recompose"], sm["slicing"],
+                        t_own, t_ven, t_ven / ms, "native" if slower else "emulate"))
+        del dA, dB, dC, gm
+        torch.cuda.empty_cache()
+    with open(os.path.join(OUT, "throughput_shapes.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--shapes", action="store_true")
     ap.add_argument("--sizes", default="8192")
     ap.add_argument("--phis", default="0.1,1,2")
     ap.add_argument("--reps", type=int, default=5)
@@ -70,6 +112,10 @@ def main():
     os.makedirs(OUT, exist_ok=True)
     h = g.Handle(0)
     st = torch.cuda.current_stream().cuda_stream
+    if args.shapes:
+        shapes(torch, g, h, args.reps)
+        h.close()
+        return
     for n in (int(v) for v in args.sizes.split(",")):
         flops = 2.0 * n ** 3
         tf = lambda ms: flops / (ms * 1e-3) * 1e-12
