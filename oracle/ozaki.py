@@ -26,8 +26,8 @@ Encoding"; exact reconstruction of floor(a*2^q); brute-force ESC; coarse >= exac
 exact; closed-form ESC of the generalised Test-2 matrices (2b+1); power-of-two scaling
 invariance; integer matrices reproduce an int64 matmul exactly; exact rational reference.
 Parity unpinned (own choices, only the error bound applies): the run-time heuristic's
-constants, the default block length b, the slice cap, the rounding order of the FP64
-recomposition.
+cost model, its constants and its shape-only pre-check, the default block length b, the slice
+cap, the int32 k-block length, the rounding order of the FP64 recomposition.
 """
 from __future__ import annotations
 
