@@ -142,7 +142,7 @@ __device__ __forceinline__ void emit(const uint64_t (&bits)[16], int e_row, int 
     }
 }
 
-constexpr int kSliceChunksPerWg = 4;
+constexpr int kSliceChunksPerWg = 1;
 
 // Rows contiguous in memory: thread = row, lanes along rows; loads coalesce across the wave.
 // grid: (rows_p/256, (kp/16)/kSliceChunksPerWg)
