@@ -18,7 +18,7 @@
  *     frees device memory and never synchronises: a call only enqueues kernels on `stream`
  *     (a hipStream_t passed as void*) and returns.
  *   - m == 0 or n == 0: nothing is done.  k == 0 or alpha == 0: C = beta * C.
- *     Limits: m, n <= 2^22, k <= 2^21 (larger sizes are an argument error).
+ *     Limits: m, n <= 2^22, k <= 2^21, m*n*k <= 2^52 (larger sizes are an argument error).
  *   - Return values report host-side argument errors only.  Numerical conditions (Inf/NaN in
  *     the inputs, exponent span too wide, emulation predicted slower) are never errors: they
  *     select the native FP64 path and are recorded in *result.
@@ -52,7 +52,9 @@ typedef enum {
                                predicts emulation to be slower */
     OZ_FORCED_GUARDED = 1,  /* scan + ESC run (their cost is paid), S forced from max_bits; only
                                Inf/NaN selects the native path */
-    OZ_FIXED_GUARDED = 2,   /* S from max_bits; native path on Inf/NaN or target_bits + ESC > max_bits */
+    OZ_FIXED_GUARDED = 2,   /* S from max_bits; native path on Inf/NaN, on target_bits + ESC > max_bits, or
+                               when the S slices cannot carry target_bits + ESC (S slices carry 8S - 2
+                               magnitude bits: ceil((target_bits + ESC + 2) / 8) > S) */
     OZ_FIXED_UNGUARDED = 3, /* S from max_bits; no Inf/NaN test, no ESC, never falls back */
     OZ_NATIVE = 4           /* always the FP64-MFMA GEMM */
 } oz_mode_t;
@@ -92,8 +94,15 @@ typedef struct {
     int64_t fixed_ns;
 } oz_heuristic_t;
 
-/* Creates a handle bound to HIP device `device` (must be gfx950).  Host memory only. */
+/* Section "GPU-Resident Integration": the whole decision process lives on the device, so the
+ * host-side state is small.  Creates a handle bound to HIP device `device` (must be gfx950): the
+ * device's compute-unit count, the cost-model constants of the run-time heuristic and the event
+ * pool of the stage timer.  Allocates host memory only; *handle is NULL on failure.
+ * Errors: OZ_ERR_ARG (handle NULL), OZ_ERR_DEVICE (no such device / not gfx950). */
 oz_status_t oz_create(oz_handle_t* handle, int device);
+
+/* Releases what oz_create made (host memory, events).  Work already enqueued with the handle is
+ * not waited for: it only references caller-owned device memory.  OZ_ERR_ARG on NULL. */
 oz_status_t oz_destroy(oz_handle_t handle);
 
 /* Fills *opts with the defaults: OZ_DYNAMIC, target 53, max 200, slices 0, esc_block 0, heuristic 1. */
@@ -102,14 +111,29 @@ void oz_default_opts(oz_opts_t* opts);
 /* Replaces the heuristic's constants (defaults are calibrated for MI355X). */
 oz_status_t oz_set_heuristic(oz_handle_t handle, const oz_heuristic_t* model);
 
-/* Bytes of device workspace oz_dgemm needs for this problem and these options (sized for the
- * largest slice count the options allow).  Returns 0 on invalid arguments. */
+/* Sections "Unsigned Slice Encoding" and "ADP" fix what a call stores between its steps: the
+ * row/column exponents, the per-block Max/Min exponent tables of the coarsened ESC, the S slice
+ * planes of each operand and the S anti-diagonal sums per k-block.  Returns the bytes of device
+ * workspace oz_dgemm needs for this problem and these options, sized for the largest slice count
+ * the options allow (fixed modes: the S of max_bits/slices; OZ_DYNAMIC: the S of max_bits, or the
+ * largest S the cost model still calls faster when heuristic = 1).  Host-only, no device access.
+ * Returns 0 on invalid arguments. */
 size_t oz_dgemm_workspace_bytes(oz_handle_t handle, char transa, char transb,
                                 int64_t m, int64_t n, int64_t k, const oz_opts_t* opts);
 
-/* The call.  workspace: device, 256-byte aligned, >= oz_dgemm_workspace_bytes(...); its
- * contents are scratch.  result: device, may be NULL.  Calls sharing a workspace must be
- * ordered on one stream. */
+/* The emulated DGEMM with guardrails: the flowchart of the GEMM decision process, steps in the
+ * order of sections "Pre-processing and Safety Checks" (Inf/NaN scan), "Exponent Span
+ * Estimation" (block Max/Min tables, coarsened ESC), "Heuristic run time Selection" (verdict),
+ * "Unsigned Slice Encoding" (slicing), "FP64 Emulation on Low-Precision Units" (slice-pair INT8
+ * GEMMs, FP64 recomposition), with the native FP64 GEMM as the other branch.  All kernels are
+ * enqueued on `stream`; the ones after the verdict read the device-resident record.
+ *   A, B, C: device, column-major, leading dimensions in elements (see Conventions above).
+ *   workspace: device, 256-byte aligned, >= oz_dgemm_workspace_bytes(...); contents are scratch
+ *     on entry and hold the intermediates afterwards (oz_dgemm_layout).  Calls sharing a
+ *     workspace must be ordered on one stream.
+ *   result: device oz_result_t written by the verdict kernel, may be NULL.
+ * Errors (nothing is enqueued): OZ_ERR_ARG, OZ_ERR_WORKSPACE, OZ_ERR_DEVICE; OZ_ERR_HIP if a
+ * launch failed. */
 oz_status_t oz_dgemm(oz_handle_t handle, void* stream, char transa, char transb,
                      int64_t m, int64_t n, int64_t k, double alpha,
                      const double* A, int64_t lda, const double* B, int64_t ldb,
@@ -162,7 +186,11 @@ oz_status_t oz_dgemm_layout(oz_handle_t handle, char transa, char transb,
 oz_status_t oz_profile_enable(oz_handle_t handle, int32_t max_calls);
 oz_status_t oz_profile_read(oz_handle_t handle, int32_t call, float* stage_ms);
 
-/* Stand-alone native FP64-MFMA GEMM (the fallback kernel on its own), same conventions. */
+/* The fallback branch of the decision process on its own (sections "Pre-processing and Safety
+ * Checks" and "Heuristic run time Selection": the native FP64 GEMM that Inf/NaN inputs, too wide
+ * an exponent span or an inefficient slice count route to), and the baseline the paper's speed-ups
+ * are quoted against.  Same conventions as oz_dgemm; no workspace, no record; only enqueues.
+ * Errors: OZ_ERR_ARG, OZ_ERR_DEVICE, OZ_ERR_HIP. */
 oz_status_t oz_native_dgemm(oz_handle_t handle, void* stream, char transa, char transb,
                             int64_t m, int64_t n, int64_t k, double alpha,
                             const double* A, int64_t lda, const double* B, int64_t ldb,

@@ -221,7 +221,10 @@ def verdict(mode: int, target_bits: int, max_bits: int, slices_override: int, in
     DYNAMIC         S from target_bits + ESC; falls back on Inf/NaN, on required_bits >
                     max_bits, or when the heuristic predicts emulation to be slower.
     FORCED_GUARDED  scan and ESC run but S is forced; only Inf/NaN falls back.
-    FIXED_GUARDED   S fixed; falls back on Inf/NaN or when target_bits + ESC > max_bits.
+    FIXED_GUARDED   S fixed; falls back on Inf/NaN, when target_bits + ESC > max_bits, or when
+                    the fixed S slices cannot hold target_bits + ESC (the dynamic rule would
+                    ask for more slices than S: with the headroom bit S slices carry 8S - 2
+                    magnitude bits, so "55 bits" = 7 slices carry 54).
     FIXED_UNGUARDED S fixed; never falls back.
     NATIVE          always the FP64 GEMM."""
     S_fixed = slices_override if slices_override > 0 else slices_for_bits(max_bits)
@@ -236,7 +239,7 @@ def verdict(mode: int, target_bits: int, max_bits: int, slices_override: int, in
     if mode == MODE_FORCED_GUARDED:
         return Verdict(0, REASON_NONE, S_fixed, esc, required, 0)
     if mode == MODE_FIXED_GUARDED:
-        if required > max_bits:
+        if required > max_bits or slices_dynamic(target_bits, esc) > S_fixed:
             return Verdict(1, REASON_BITS, 0, esc, required, 0)
         return Verdict(0, REASON_NONE, S_fixed, esc, required, 0)
     if mode == MODE_DYNAMIC:

@@ -67,8 +67,13 @@ int slice_cap(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int6
 
 bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int64_t k, Problem& p) {
     if (m < 0 || n < 0 || k < 0) return false;
-    // launch grids carry k/64 and n/128 in a 16-bit dimension
+    // per-dimension limits keep every launch grid inside what the device accepts (the kernels that
+    // put k or n on grid.y launch in slabs); the limit on the product keeps 2mnk and the cost
+    // model's other terms inside int64
     if (m > kMaxRows || n > kMaxRows || k > kMaxK) return false;
+    if (static_cast<unsigned __int128>(m) * static_cast<unsigned __int128>(n) * static_cast<unsigned __int128>(k) >
+        static_cast<unsigned __int128>(kMaxMnk))
+        return false;
     p.m = m; p.n = n; p.k = k;
     p.mp = round_up(m > 0 ? m : 1, kRowPad);
     p.np = round_up(n > 0 ? n : 1, kRowPad);
@@ -291,6 +296,9 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < L.total_bytes)
         return OZ_ERR_WORKSPACE;
 
+    if (k != 0 && alpha != 0.0 && (!A || !B)) return OZ_ERR_ARG;
+
+    // every argument has been accepted: from here on the call only enqueues
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Workspace w = bind(workspace, p, L);
     StageClock clk(h, st);
@@ -302,7 +310,6 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
         for (int s = 0; s < OZ_NUM_STAGES; ++s) clk.done(s);
         return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
     }
-    if (!A || !B) return OZ_ERR_ARG;
 
     // element (r, l) of op(A) (r = i) and of op(B) (r = j) at base[r*stride_r + l*stride_l]
     const int64_t a_sr = ta ? lda : 1, a_sl = ta ? 1 : lda;

@@ -234,7 +234,12 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
     const int T = small ? 64 : 128;
     const int ntm = int((m + T - 1) / T), ntn = int((n + T - 1) / T);
     const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
-    const bool edge = (m % T) || (n % T) || (k % kDK);
+    // the interior path keeps each lane's offset inside a tile in 32 bits (at most 15 leading
+    // dimensions plus a row of the tile, in bytes); operands cut out of a very large parent matrix
+    // take the bounds-checked path, which indexes in 64 bits
+    const int64_t ld_max = lda > ldb ? lda : ldb;
+    const bool wide_ld = (15 * ld_max + 256) * 8 >= (int64_t(1) << 32);
+    const bool edge = (m % T) || (n % T) || (k % kDK) || wide_ld;
 #define OZ_DG_T(AC, BC, TT)                                                                                    \
     {                                                                                                          \
         if (edge) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, true, TT>), grid, block, 0, st, rec, m, n, k,   \

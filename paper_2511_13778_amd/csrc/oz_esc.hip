@@ -279,14 +279,17 @@ __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int 
         const int esc = min(rec->span_max + 1, kEscCap);
         r.esc = esc;
         r.required_bits = o.target_bits + esc;
+        // slices that hold required_bits, the sign and the headroom bit
+        int S = (o.target_bits + esc + 1 + kHeadroomBits + 7) / 8;
         if (o.mode == OZ_FORCED_GUARDED) {
             r.slices_used = s_fixed;
         } else if (r.required_bits > o.max_bits) {
             r.fallback = 1; r.reason = 2;
         } else if (o.mode == OZ_FIXED_GUARDED) {
-            r.slices_used = s_fixed;
+            // the fixed slices must really carry the bits (S slices carry 8S - 2: "55 bits" is 54)
+            if (S > s_fixed) { r.fallback = 1; r.reason = 2; }
+            else r.slices_used = s_fixed;
         } else {
-            int S = (o.target_bits + esc + 1 + kHeadroomBits + 7) / 8;
             S = max(1, min(S, kMaxSlices));
             bool slower = false;
             if (o.heuristic) {
@@ -301,8 +304,10 @@ __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int 
             else r.slices_used = S;
         }
     }
-    // the workspace holds s_cap slice planes; the host sized it so that this never binds
-    if (!r.fallback && r.slices_used > s_cap) r.slices_used = s_cap;
+    // The workspace holds s_cap slice planes and the host sized it for the largest count these options
+    // can select, so this never binds; if it ever did, running with fewer slices would lose bits
+    // silently, so the call goes native and says why.
+    if (!r.fallback && r.slices_used > s_cap) { r.fallback = 1; r.reason = 2; r.slices_used = 0; }
     rec->res = r;
     if (user_result) *user_result = r;
 }

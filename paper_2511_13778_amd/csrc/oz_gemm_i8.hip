@@ -47,8 +47,8 @@ static_assert(kDmaPerStage == 8, "the vmcnt immediates below assume 8 DMA instru
 
 constexpr int kRoundTiles = 32;       // workgroups an XCD runs at a time: 32 CUs, one workgroup each
 constexpr int kMaxSyncSpins = 384;    // upper bound of the wait for the other workgroups of a round
-constexpr int kMidSyncMinK = 12288;
-constexpr int kMinSplitSteps = 8;     // a part of a split k range keeps at least this many K steps   // from this k on, workgroups also wait after every anti-diagonal
+constexpr int kMidSyncMinK = 12288;   // from this k on, workgroups also wait after every anti-diagonal
+constexpr int kMinSplitSteps = 8;     // a part of a split k range keeps at least this many K steps
 
 // Records this workgroup's arrival at *counter and, if `wait`, waits (bounded, about half a
 // millisecond) until `target` workgroups have arrived.  The wait only improves cache locality:

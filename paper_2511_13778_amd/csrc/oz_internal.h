@@ -15,6 +15,7 @@ constexpr int kEscCap = 4096;         // reported ESC is clamped to this
 constexpr int kDefaultEscBlock = 64;
 constexpr int64_t kMaxRows = int64_t(1) << 22;   // largest m, n
 constexpr int64_t kMaxK = int64_t(1) << 21;      // largest k
+constexpr int64_t kMaxMnk = int64_t(1) << 52;    // largest m*n*k: the cost model multiplies 2mnk by up to 351 pairs in int64
 
 // Exponents are kept as int16 in the block tables.  Real exponents lie in [-1074, 1023].
 // kExpZeroInMin: Min of a block that holds a zero (exp(0) = -infinity).

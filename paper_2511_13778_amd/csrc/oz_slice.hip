@@ -143,12 +143,14 @@ __device__ __forceinline__ void emit(const uint64_t (&bits)[16], int e_row, int 
 }
 
 constexpr int kSliceChunksPerWg = 1;
+constexpr int64_t kMaxGridY = 65535;   // grid.y limit the device reports
 
 // Rows contiguous in memory: thread = row, lanes along rows; loads coalesce across the wave.
-// grid: (rows_p/256, (kp/16)/kSliceChunksPerWg)
+// grid: (rows_p/256, chunks of this launch / kSliceChunksPerWg); chunk0 = first 16-k chunk of the launch
 __global__ __launch_bounds__(256) void slice_rows_contig_kernel(
     const double* __restrict__ X, int64_t stride_l, int64_t rows, int64_t rows_p, int64_t k,
-    int64_t kp, const int32_t* __restrict__ e_row, int8_t* __restrict__ out, const Record* rec) {
+    int64_t kp, const int32_t* __restrict__ e_row, int8_t* __restrict__ out, const Record* rec,
+    int64_t chunk0) {
     if (rec->res.fallback) return;
     const int S = rec->res.slices_used;
     const int64_t r = int64_t(blockIdx.x) * 256 + threadIdx.x;
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(256) void slice_rows_contig_kernel(
     const bool row_ok = r < rows;
     const uint64_t* src = reinterpret_cast<const uint64_t*>(X) + (row_ok ? r : rows - 1);
     for (int cc = 0; cc < kSliceChunksPerWg; ++cc) {
-        const int64_t c = int64_t(blockIdx.y) * kSliceChunksPerWg + cc;
+        const int64_t c = chunk0 + int64_t(blockIdx.y) * kSliceChunksPerWg + cc;
         uint64_t bits[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -208,9 +210,13 @@ void launch_slice(hipStream_t st, const double* X, int64_t stride_r, int64_t str
                   int64_t rows_p, const Problem& p, const int32_t* e_row, int8_t* slices,
                   const Record* rec) {
     if (stride_r == 1) {
-        const unsigned gy = unsigned(p.kp / 16 / kSliceChunksPerWg);
-        hipLaunchKernelGGL(slice_rows_contig_kernel, dim3(unsigned(rows_p / 256), gy), dim3(256), 0, st, X,
-                           stride_l, rows, rows_p, p.k, p.kp, e_row, slices, rec);
+        // k chunks ride on grid.y: the longest k (2^21) has 131072 of them, launched in slabs
+        const int64_t groups = p.kp / 16 / kSliceChunksPerWg;
+        for (int64_t g0 = 0; g0 < groups; g0 += kMaxGridY) {
+            const unsigned gy = unsigned(groups - g0 < kMaxGridY ? groups - g0 : kMaxGridY);
+            hipLaunchKernelGGL(slice_rows_contig_kernel, dim3(unsigned(rows_p / 256), gy), dim3(256), 0, st, X,
+                               stride_l, rows, rows_p, p.k, p.kp, e_row, slices, rec, g0 * kSliceChunksPerWg);
+        }
     } else {
         hipLaunchKernelGGL(slice_k_contig_kernel, dim3(unsigned(rows_p / 64), unsigned(p.kp / 64)), dim3(256),
                            0, st, X, stride_r, rows, rows_p, p.k, p.kp, e_row, slices, rec);

@@ -1,10 +1,17 @@
 """Writes tests/golden/fullsize_esc.txt: the coarsened ESC (block length 64) of the full-size
 seeded workloads, computed by the CPU oracle only (it takes minutes at these sizes, which is why
-the values are stored).  Run from the repository root:  python tests/golden/make_fullsize_esc.py
+the values are stored).  Run from the repository root:
+
+    python tests/golden/make_fullsize_esc.py [workload ...]
+
+The ESC is 1 + a maximum over all (row of A, column of B) pairs, clamped; so the oracle is called
+on slabs of rows of A (each against the whole of B) and the slab results are combined with max():
+the same number as one call on the whole matrices, in bounded memory and on several host cores.
 """
 import os
 import sys
 import time
+from concurrent.futures import ProcessPoolExecutor
 
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
@@ -13,12 +20,40 @@ from oracle import ozaki as oz                              # noqa: E402
 from paper_2511_13778_amd import workloads as wl            # noqa: E402
 
 CASES = {
-    # name: (generator, kwargs)
+    # name: generator of (A, B)
     "lognormal_4096_phi0.5_seed2": lambda: wl.lognormal_spread(4096, 4096, 4096, 0.5, seed=2),
+    "lognormal_8192_phi0.1_seed3": lambda: wl.lognormal_spread(8192, 8192, 8192, 0.1, seed=3)[:2],
     "lognormal_8192_phi1_seed4": lambda: wl.lognormal_spread(8192, 8192, 8192, 1.0, seed=4)[:2],
+    "lognormal_8192_phi2_seed5": lambda: wl.lognormal_spread(8192, 8192, 8192, 2.0, seed=5)[:2],
+    "lognormal_16384_phi1_seed4": lambda: wl.lognormal_spread(16384, 16384, 16384, 1.0, seed=4)[:2],
     "rowscaled_1024x1024x65536_seed6": lambda: wl.row_scaled(1024, 65536, 1024, seed=6)[:2],
     "rowscaled_32768x256x8192_seed6": lambda: wl.row_scaled(32768, 8192, 256, seed=6)[:2],
+    "rowscaled_16384x16384x512_seed6": lambda: wl.row_scaled(16384, 512, 16384, seed=6)[:2],
+    "widespan_2048_seed7": lambda: wl.wide_span(2048, 2048, 2048, seed=7),
+    "rank1_2048_seed9": lambda: wl.rank1_cancel(2048, 2048, 2048, seed=9),
 }
+
+SLAB_ELEMS = 1 << 24          # (rows of a slab) x n: bounds the oracle's m x n temporaries
+WORKERS = int(os.environ.get("ESC_WORKERS", "4"))
+
+_A = _B = None                # inherited by the forked workers
+
+
+def _slab(r):
+    return oz.esc_coarse(_A[r[0]:r[1]], _B, 64)
+
+
+def esc_by_slabs(A, B):
+    global _A, _B
+    _A, _B = A, B
+    m, n = A.shape[0], B.shape[1]
+    rows = max(1, min(m, SLAB_ELEMS // n))
+    slabs = [(r0, min(m, r0 + rows)) for r0 in range(0, m, rows)]
+    if len(slabs) == 1:
+        return _slab(slabs[0])
+    with ProcessPoolExecutor(max_workers=min(WORKERS, len(slabs))) as pool:
+        return max(pool.map(_slab, slabs))
+
 
 if __name__ == "__main__":
     only = sys.argv[1:]
@@ -34,7 +69,7 @@ if __name__ == "__main__":
             continue
         A, B = gen()[:2]
         t0 = time.time()
-        have[name] = oz.esc_coarse(A, B, 64)
+        have[name] = esc_by_slabs(A, B)
         print(name, have[name], "%.0f s" % (time.time() - t0), flush=True)
         with open(out, "w") as f:
             f.write("# coarsened ESC (b = 64) of the full-size seeded workloads, written by make_fullsize_esc.py\n"

@@ -113,10 +113,23 @@ def test_verdict_table():
     assert (v.fallback, v.slices_used, v.esc, v.required_bits) == (0, 7, 30, 83)
     v = V(oz.MODE_FORCED_GUARDED, 53, 55, 0, True, -1, 64, 64, 64)
     assert (v.fallback, v.reason, v.infnan) == (1, oz.REASON_INFNAN, 1)
-    # fixed + guard: falls back when target + ESC exceeds the available bits
-    assert V(oz.MODE_FIXED_GUARDED, 53, 55, 0, False, 2, 8, 8, 8).fallback == 0
-    v = V(oz.MODE_FIXED_GUARDED, 53, 55, 0, False, 3, 8, 8, 8)
-    assert (v.fallback, v.reason) == (1, oz.REASON_BITS)
+    # fixed + guard: falls back when target + ESC exceeds the available bits.  Seven slices carry
+    # 8*7 - 2 = 54 magnitude bits (one headroom bit), so required_bits == max_bits == 55 is already
+    # one bit more than they hold: the guard must trip exactly where the dynamic rule asks for 8
+    assert V(oz.MODE_FIXED_GUARDED, 53, 55, 0, False, 1, 8, 8, 8).fallback == 0
+    for esc in (2, 3):
+        v = V(oz.MODE_FIXED_GUARDED, 53, 55, 0, False, esc, 8, 8, 8)
+        assert (v.fallback, v.reason, v.required_bits) == (1, oz.REASON_BITS, 53 + esc)
+    for mb in (39, 55, 63, 71):
+        S = oz.slices_for_bits(mb)
+        for esc in range(1, 30):
+            v = V(oz.MODE_FIXED_GUARDED, 53, mb, 0, False, esc, 8, 8, 8)
+            assert (v.fallback == 0) == (53 + esc <= mb and oz.slices_dynamic(53, esc) <= S)
+            if not v.fallback:      # an accepted call never runs with fewer slices than the dynamic rule
+                assert v.slices_used >= oz.slices_dynamic(53, esc)
+    # an explicit slice count below what max_bits implies is held to the same capacity rule
+    assert V(oz.MODE_FIXED_GUARDED, 20, 55, 4, False, 9, 8, 8, 8).fallback == 0      # 20 + 9 + 2 = 31 <= 32
+    assert V(oz.MODE_FIXED_GUARDED, 20, 55, 4, False, 11, 8, 8, 8).fallback == 1     # 33 > 32
     # dynamic: S grows with ESC
     assert V(oz.MODE_DYNAMIC, 53, 200, 0, False, 1, 8, 8, 8).slices_used == 7
     assert V(oz.MODE_DYNAMIC, 53, 200, 0, False, 9, 8, 8, 8).slices_used == 8
