@@ -43,6 +43,7 @@ NEG_INF_BELOW = -(1 << 19)  # any exponent (or exponent sum) below this is -infi
 ESC_CAP = 4096             # reported ESC is min(ESC, ESC_CAP)
 MAX_SLICES = 26            # 200 mantissa bits (section "Numerical Accuracy", aspect A2)
 DEFAULT_ESC_BLOCK = 64
+TILE = 256                 # edge of the blocks of C that may take their own slice count
 
 MODE_DYNAMIC, MODE_FORCED_GUARDED, MODE_FIXED_GUARDED, MODE_FIXED_UNGUARDED, MODE_NATIVE = range(5)
 REASON_NONE, REASON_INFNAN, REASON_BITS, REASON_HEURISTIC, REASON_NATIVE = range(5)
@@ -127,16 +128,16 @@ def block_minmax(E: np.ndarray, b: int, axis: int):
     return tuple(np.moveaxis(t, -1, axis) for t in (mx, mn, live, full))
 
 
-def esc_coarse(A: np.ndarray, B: np.ndarray, b: int = DEFAULT_ESC_BLOCK) -> int:
-    """1 + max_ij ( eA_i + eB_j - zt_ij ),
+def coarse_span(A: np.ndarray, B: np.ndarray, b: int = DEFAULT_ESC_BLOCK) -> np.ndarray:
+    """m x n matrix of  eA_i + eB_j - zt_ij  (the coarsened exponent span of every dot product),
     zt_ij = max_g max( Max(xb_g) + Min(yb_g), Min(xb_g) + Max(yb_g) ).
 
     A zero has exponent -infinity: it never sets a block's Max, and it makes the block's Min
     -infinity, which removes that candidate (the proof that the coarse zt never exceeds the
     true exp(z_r) pairs the entry attaining Max(xb_g) with its partner in yb_g, which must
     therefore be non-zero).  A dot product in which every block has an all-zero side is
-    identically zero and contributes 0, as in esc_exact.  Any other pair left without a
-    candidate is unbounded and is reported as ESC_CAP."""
+    identically zero and has span 0, as in esc_exact.  Any other pair left without a
+    candidate is unbounded and gets ESC_CAP."""
     EA, EB = exponents(A), exponents(B)
     eA, eB = EA.max(axis=1), EB.max(axis=0)
     Amax, Amin, Alive, Afull = block_minmax(EA, b, axis=1)          # m x G
@@ -154,8 +155,30 @@ def esc_coarse(A: np.ndarray, B: np.ndarray, b: int = DEFAULT_ESC_BLOCK) -> int:
             have |= ok
         dead &= ~(Alive[:, g][:, None] & Blive[g, :][None, :])
     span = np.where(have, eA[:, None] + eB[None, :] - zt, ESC_CAP)
-    span = np.where(dead, 0, span)
+    return np.where(dead, 0, span)
+
+
+def esc_coarse(A: np.ndarray, B: np.ndarray, b: int = DEFAULT_ESC_BLOCK) -> int:
+    """1 + max_ij of coarse_span, clamped to ESC_CAP: the coarsened ESC of the whole product."""
+    span = coarse_span(A, B, b)
     return min(max(int(span.max(initial=0)), 0) + 1, ESC_CAP)
+
+
+def esc_coarse_tiles(A: np.ndarray, B: np.ndarray, b: int = DEFAULT_ESC_BLOCK, tile: int = 256) -> np.ndarray:
+    """ceil(m/tile) x ceil(n/tile) matrix: the coarsened ESC of every tile x tile block of C taken
+    on its own, i.e. 1 + the maximum of coarse_span over the dot products of that block only.
+    The row and column exponents, and hence the spans, are those of the whole product: a tile's
+    rows are still aligned to the maximum of the entire row of A.  (Section "Limitations and
+    Future Directions": tighter estimates; the ESC is a per-dot-product quantity, section "ESC",
+    and nothing forces one slice count on all of C.)"""
+    span = coarse_span(A, B, b)
+    m, n = span.shape
+    out = np.zeros((-(-m // tile), -(-n // tile)), dtype=np.int64)
+    for ti in range(out.shape[0]):
+        for tj in range(out.shape[1]):
+            blk = span[ti * tile:(ti + 1) * tile, tj * tile:(tj + 1) * tile]
+            out[ti, tj] = min(max(int(blk.max(initial=0)), 0) + 1, ESC_CAP)
+    return out
 
 
 # --------------------------------------------------------------------------------------
@@ -195,9 +218,12 @@ class HeuristicModel:
     bytes_per_ns: int = 4000
     fixed_ns: int = 60000
 
-    def emulation_slower(self, S: int, m: int, n: int, k: int) -> bool:
+    def emulation_slower(self, S: int, m: int, n: int, k: int, pairs: int | None = None) -> bool:
+        """S: slice count (sets the streaming cost); pairs: slice-pair products per tile of C,
+        S(S+1)/2 unless the tiles of C take different slice counts (then the mean, rounded up)."""
         flops = 2 * m * n * k
-        pairs = S * (S + 1) // 2
+        if pairs is None:
+            pairs = S * (S + 1) // 2
         stream = (8 + S) * (m * k + k * n) + (8 * S + 16) * m * n
         t_emu = self.fixed_ns + (flops // self.int8_ops_per_ns) * pairs + stream // self.bytes_per_ns
         t_f64 = flops // self.fp64_flops_per_ns
@@ -208,15 +234,29 @@ class HeuristicModel:
 class Verdict:
     fallback: int
     reason: int
-    slices_used: int
+    slices_used: int        # S; with per-tile slice counts the largest of them
     esc: int
     required_bits: int
     infnan: int
+    slices_min: int = 0     # smallest slice count of any tile of C (== slices_used without per-tile counts)
+    pair_tiles: int = 0     # slice-pair products of TILE x TILE blocks of C the call multiplies, summed over tiles
+
+
+def pairs_of(S: int) -> int:
+    return S * (S + 1) // 2
+
+
+def tile_count(m: int, n: int, tile: int = TILE) -> int:
+    return (-(-m // tile)) * (-(-n // tile))
 
 
 def verdict(mode: int, target_bits: int, max_bits: int, slices_override: int, infnan: bool,
-            esc: int, m: int, n: int, k: int, heuristic: HeuristicModel | None = None) -> Verdict:
+            esc: int, m: int, n: int, k: int, heuristic: HeuristicModel | None = None,
+            tile_esc: np.ndarray | None = None) -> Verdict:
     """The decision record.  `esc` is -1 when no ESC was computed (unguarded / native modes).
+    tile_esc (DYNAMIC only): the ESC of every TILE x TILE block of C (esc_coarse_tiles); each block
+    then takes slices_dynamic(target_bits, its own ESC) slices, `esc` must be their maximum, and
+    the cost model is fed the mean number of slice-pair products per block.
 
     DYNAMIC         S from target_bits + ESC; falls back on Inf/NaN, on required_bits >
                     max_bits, or when the heuristic predicts emulation to be slower.
@@ -231,25 +271,39 @@ def verdict(mode: int, target_bits: int, max_bits: int, slices_override: int, in
     S_fixed = min(S_fixed, MAX_SLICES)
     if mode == MODE_NATIVE:
         return Verdict(1, REASON_NATIVE, 0, -1, 0, 0)
+    nt = tile_count(m, n)
     if mode == MODE_FIXED_UNGUARDED:
-        return Verdict(0, REASON_NONE, S_fixed, -1, 0, 0)
+        return Verdict(0, REASON_NONE, S_fixed, -1, 0, 0, S_fixed, nt * pairs_of(S_fixed))
     if infnan:
         return Verdict(1, REASON_INFNAN, 0, -1, 0, 1)
     required = target_bits + esc
     if mode == MODE_FORCED_GUARDED:
-        return Verdict(0, REASON_NONE, S_fixed, esc, required, 0)
+        return Verdict(0, REASON_NONE, S_fixed, esc, required, 0, S_fixed, nt * pairs_of(S_fixed))
     if mode == MODE_FIXED_GUARDED:
         if required > max_bits or slices_dynamic(target_bits, esc) > S_fixed:
             return Verdict(1, REASON_BITS, 0, esc, required, 0)
-        return Verdict(0, REASON_NONE, S_fixed, esc, required, 0)
+        return Verdict(0, REASON_NONE, S_fixed, esc, required, 0, S_fixed, nt * pairs_of(S_fixed))
     if mode == MODE_DYNAMIC:
         if required > max_bits:
             return Verdict(1, REASON_BITS, 0, esc, required, 0)
         S = min(slices_dynamic(target_bits, esc), MAX_SLICES)
-        if heuristic is not None and heuristic.emulation_slower(S, m, n, k):
+        if tile_esc is None:
+            S_min, pair_tiles = S, nt * pairs_of(S)
+        else:
+            assert tile_esc.size == nt and int(tile_esc.max()) == esc
+            S_t = [min(slices_dynamic(target_bits, int(e)), MAX_SLICES) for e in tile_esc.ravel()]
+            S_min, pair_tiles = min(S_t), sum(pairs_of(x) for x in S_t)
+        pairs_mean = -(-pair_tiles // nt)                     # rounded up
+        if heuristic is not None and heuristic.emulation_slower(S, m, n, k, pairs_mean):
             return Verdict(1, REASON_HEURISTIC, 0, esc, required, 0)
-        return Verdict(0, REASON_NONE, S, esc, required, 0)
+        return Verdict(0, REASON_NONE, S, esc, required, 0, S_min, pair_tiles)
     raise ValueError("unknown mode")
+
+
+def tile_slices(target_bits: int, tile_esc: np.ndarray) -> np.ndarray:
+    """Slice count of every TILE x TILE block of C from its own ESC."""
+    f = np.vectorize(lambda e: min(slices_dynamic(target_bits, int(e)), MAX_SLICES))
+    return f(tile_esc).astype(np.int64)
 
 
 def shape_only_fallback(mode: int, target_bits: int, m: int, n: int, k: int,
@@ -454,6 +508,23 @@ def recompose(P: np.ndarray, eA: np.ndarray, eB: np.ndarray) -> np.ndarray:
         return np.ldexp(R, scale.astype(np.int32))
 
 
+def recompose_tiles(P: np.ndarray, eA: np.ndarray, eB: np.ndarray, S_tile: np.ndarray,
+                    tile: int = TILE) -> np.ndarray:
+    """recompose() with a slice count per tile x tile block of C: block (ti, tj) uses the anti-
+    diagonals d < S_tile[ti, tj] of P only, i.e. the leading S_tile digits of every row of A and
+    column of B and the pairs s + t <= S_tile - 1.  The digits are those of the one decomposition
+    into max(S_tile) slices: its leading S' digits represent the entry to within 0.51 units of
+    digit S' (the dropped tail is a signed number), which is what S' slices need to deliver."""
+    nkb, S, m, n = P.shape
+    out = np.zeros((m, n), dtype=np.float64)
+    for ti in range(S_tile.shape[0]):
+        for tj in range(S_tile.shape[1]):
+            r = slice(ti * tile, min(m, (ti + 1) * tile))
+            c = slice(tj * tile, min(n, (tj + 1) * tile))
+            out[r, c] = recompose(P[:, :int(S_tile[ti, tj]), r, c], eA[r], eB[c])
+    return out
+
+
 def axpby(alpha: float, AB: np.ndarray, beta: float, C: np.ndarray | None) -> np.ndarray:
     """alpha*AB + beta*C with every product and the sum rounded separately; C is not read
     when beta == 0."""
@@ -476,6 +547,7 @@ class Trace:
     Bs: np.ndarray | None = None       # S x n x k
     P: np.ndarray | None = None        # nkb x S x m x n
     C: np.ndarray | None = None
+    S_tile: np.ndarray | None = None   # slice count per TILE x TILE block of C (per-tile mode only)
 
 
 def native_gemm(alpha, A, B, beta, C):
@@ -489,9 +561,12 @@ def emulated_dgemm(A: np.ndarray, B: np.ndarray, alpha: float = 1.0, beta: float
                    C: np.ndarray | None = None, *, mode: int = MODE_FORCED_GUARDED,
                    target_bits: int = 53, max_bits: int = 55, slices: int = 0,
                    esc_block: int = DEFAULT_ESC_BLOCK,
-                   heuristic: HeuristicModel | None = None, keep: bool = True) -> Trace:
+                   heuristic: HeuristicModel | None = None, keep: bool = True,
+                   per_tile: bool = False, tile: int = TILE) -> Trace:
     """C = alpha*A*B + beta*C through the decision process of the paper's flowchart:
-    CheckInfNaN(A), CheckInfNaN(B) -> ESC(A,B) -> verdict -> emulated or native GEMM."""
+    CheckInfNaN(A), CheckInfNaN(B) -> ESC(A,B) -> verdict -> emulated or native GEMM.
+    per_tile (DYNAMIC only): every tile x tile block of C takes the slice count of its own ESC
+    (`tile` other than TILE is for small test cases; the verdict's tile counts assume TILE)."""
     A = np.asarray(A, dtype=np.float64)
     B = np.asarray(B, dtype=np.float64)
     m, k = A.shape
@@ -503,8 +578,14 @@ def emulated_dgemm(A: np.ndarray, B: np.ndarray, alpha: float = 1.0, beta: float
         return Trace(Verdict(1, REASON_HEURISTIC, 0, -1, 0, 0), C=native_gemm(alpha, A, B, beta, C))
     guarded = mode in (MODE_DYNAMIC, MODE_FORCED_GUARDED, MODE_FIXED_GUARDED)
     infnan = guarded and (has_inf_nan(A) or has_inf_nan(B))
-    esc = esc_coarse(A, B, esc_block) if (guarded and not infnan) else -1
-    v = verdict(mode, target_bits, max_bits, slices, infnan, esc, m, n, k, heuristic)
+    tiled = per_tile and mode == MODE_DYNAMIC and guarded and not infnan
+    tile_esc = esc_coarse_tiles(A, B, esc_block, tile) if tiled else None
+    if tiled:
+        esc = int(tile_esc.max())
+    else:
+        esc = esc_coarse(A, B, esc_block) if (guarded and not infnan) else -1
+    v = verdict(mode, target_bits, max_bits, slices, infnan, esc, m, n, k, heuristic,
+                tile_esc if (tiled and tile == TILE) else None)
     if v.fallback:
         return Trace(v, C=native_gemm(alpha, A, B, beta, C))
     S = v.slices_used
@@ -512,7 +593,9 @@ def emulated_dgemm(A: np.ndarray, B: np.ndarray, alpha: float = 1.0, beta: float
     As = slice_rows(A, eA, S)
     Bs = slice_rows(np.ascontiguousarray(B.T), eB, S)
     P = slice_products(As, Bs)
-    out = axpby(alpha, recompose(P, eA, eB), beta, C)
+    S_tile = tile_slices(target_bits, tile_esc) if tiled else None
+    AB = recompose_tiles(P, eA, eB, S_tile, tile) if tiled else recompose(P, eA, eB)
+    out = axpby(alpha, AB, beta, C)
     if keep:
-        return Trace(v, eA, eB, As, Bs, P, out)
-    return Trace(v, C=out)
+        return Trace(v, eA, eB, As, Bs, P, out, S_tile)
+    return Trace(v, C=out, S_tile=S_tile)

@@ -14,6 +14,8 @@ inputs are U(0,1) squares and the generalised Test-2 family of section "Numerica
   wide_span            N(0,1) times 2^-300 or 2^+300, chosen per entry
   rank1_cancel         A = u v^T + 1e-12*N(0,1)
   grading_test2             A_{k,:} = x^T D P_k,  B_{:,k} = P_k^-1 D^-1 x,  x~U(1,2), D = diag(2^j)
+  wide_rows            +-U(1,2) everywhere, except a band of rows of A whose dot products with every
+                       third column of B have a large exponent span (a localised hard region)
 """
 from __future__ import annotations
 
@@ -92,3 +94,21 @@ def grading_test2(nn, b, seed):
         A[kk, :] = np.roll(xd, kk)
         B[:, kk] = np.roll(xinv, kk)
     return A, B, x
+
+
+def wide_rows(m, k, n, seed, row_lo, row_hi, spread):
+    """+-U(1,2) matrices (all exponents 0) with a band of difficult rows: each row i in [row_lo, row_hi)
+    of A keeps one entry, at a random position l0, and is scaled by 2^-spread elsewhere; B[l0, j] is
+    scaled by 2^-spread for every third column j.  The dot products (i, j) of the band with those
+    columns then have no product within `spread` bits of the row and column maxima, all others do:
+    only the blocks of C that meet the band need many mantissa bits."""
+    r = _rng(seed)
+    A = r.uniform(1.0, 2.0, (m, k)) * r.choice([-1.0, 1.0], (m, k))
+    B = r.uniform(1.0, 2.0, (k, n)) * r.choice([-1.0, 1.0], (k, n))
+    for i in range(row_lo, row_hi):
+        l0 = int(r.integers(k))
+        keep = A[i, l0]
+        A[i] = np.ldexp(A[i], -spread)
+        A[i, l0] = keep
+        B[l0, ::3] = np.ldexp(B[l0, ::3], -spread)
+    return A, B

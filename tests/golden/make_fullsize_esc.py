@@ -33,6 +33,12 @@ CASES = {
     "rank1_2048_seed9": lambda: wl.rank1_cancel(2048, 2048, 2048, seed=9),
 }
 
+# workloads whose per-block ESC table (256 x 256 blocks of C) is stored, one file each:
+# tile_esc_<name>.txt, row ti = the ESCs of blocks (ti, 0..)
+TILE_CASES = {
+    "widerows_8192_seed11": lambda: wl.wide_rows(8192, 8192, 8192, seed=11, row_lo=3000, row_hi=3100, spread=24),
+}
+
 SLAB_ELEMS = 1 << 24          # (rows of a slab) x n: bounds the oracle's m x n temporaries
 WORKERS = int(os.environ.get("ESC_WORKERS", "4"))
 
@@ -41,6 +47,23 @@ _A = _B = None                # inherited by the forked workers
 
 def _slab(r):
     return oz.esc_coarse(_A[r[0]:r[1]], _B, 64)
+
+
+def _tile_slab(r):
+    return oz.esc_coarse_tiles(_A[r[0]:r[1]], _B, 64, oz.TILE)
+
+
+def tile_esc_by_slabs(A, B):
+    """esc_coarse_tiles on slabs of whole block rows (a block's ESC only involves its own rows of A)."""
+    global _A, _B
+    _A, _B = A, B
+    m, n = A.shape[0], B.shape[1]
+    rows = max(oz.TILE, min(m, SLAB_ELEMS // n) // oz.TILE * oz.TILE)
+    slabs = [(r0, min(m, r0 + rows)) for r0 in range(0, m, rows)]
+    with ProcessPoolExecutor(max_workers=min(WORKERS, len(slabs))) as pool:
+        parts = list(pool.map(_tile_slab, slabs))
+    import numpy as np
+    return np.vstack(parts)
 
 
 def esc_by_slabs(A, B):
@@ -64,6 +87,19 @@ if __name__ == "__main__":
             if ln.strip() and not ln.startswith("#"):
                 k, v = ln.split()
                 have[k] = int(v)
+    here = os.path.dirname(os.path.abspath(__file__))
+    for name, gen in TILE_CASES.items():
+        if only and name not in only:
+            continue
+        A, B = gen()[:2]
+        t0 = time.time()
+        T = tile_esc_by_slabs(A, B)
+        print(name, "blocks", T.shape, "ESC values", sorted(set(T.ravel().tolist())), "%.0f s" % (time.time() - t0), flush=True)
+        with open(os.path.join(here, "tile_esc_%s.txt" % name), "w") as f:
+            f.write("# coarsened ESC (b = 64) of every 256 x 256 block of C, written by make_fullsize_esc.py\n"
+                    "# (CPU oracle only).  line ti = blocks (ti, 0), (ti, 1), ...\n")
+            for row in T:
+                f.write(" ".join(str(int(v)) for v in row) + "\n")
     for name, gen in CASES.items():
         if only and name not in only:
             continue
