@@ -6,9 +6,16 @@ INT8 GEMMs, FP64 recomposition (the FP64 fallback kernel is enqueued and exits a
 are synthetic, generated on the host with a fixed seed and resident in HBM before timing.
 
 Prints ONE JSON line: effective FP64 TFLOP/s = 2mnk / t for m=n=k=8192 in the "ADP forced to 55
-mantissa bits" mode, with the roofline of the dominant kernel (slice GEMM, INT8 MFMA), per-stage
-times from HIP events recorded on the call's stream, the native FP64 GEMM rates measured in the
-same run, and the CPU oracle timed on the host cores on a bounded sample.
+mantissa bits" mode, with
+  * the roofline of the dominant kernel (slice GEMM, INT8 MFMA) from HIP events recorded on the
+    call's stream, against the published peak and against the matrix unit's rate measured in the
+    same run with an MFMA-only loop (constant and random operands);
+  * per-stage times (median over the timed calls) and the HBM-bound stages against the published
+    bandwidth and against a plain copy kernel measured in the same run;
+  * the native FP64 GEMM rates (this library's kernel and the vendor's);
+  * the call as it ships (OZ_DYNAMIC with the run-time heuristic on) on the same input: which
+    route the decision process took, its time, and what the guard cost on top of the native GEMM;
+  * the CPU oracle timed on the host cores on a bounded sample (run first, before the GPU legs).
 """
 from __future__ import annotations
 
@@ -24,11 +31,12 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published
 HBM_PEAK_GBS = 8000.0
+CU_COUNT, SIMD_PER_CU, INT8_OPS_PER_CLK_SIMD = 256, 4, 2048   # 256*4*2048*2.4 GHz = the published peak
 
 
 def cpu_baseline(size: int, phi: float):
-    """The oracle as it stands, timed on a bounded sample (m=n=k=size of the same generator)."""
-    import numpy as np
+    """The oracle as it stands, timed on a bounded sample (m=n=k=size of the same generator).  Its
+    slice products run as float64 matrix products of the digit planes (numpy/BLAS threads)."""
     from oracle import ozaki as oz
     from paper_2511_13778_amd import workloads as wl
     try:
@@ -42,7 +50,8 @@ def cpu_baseline(size: int, phi: float):
     dt = time.perf_counter() - t0
     return {"value": 2.0 * size ** 3 / dt * 1e-12, "unit": "TFLOP/s (effective FP64, 2mnk/t)", "cores": int(cores),
             "kind": "oracle", "seconds": dt,
-            "sample": "same generator and mode at m=n=k=%d (full 8192^3 would take hours on the host)" % size}
+            "sample": "same generator and mode at m=n=k=%d (full 8192^3 would take hours on the host); the "
+                      "oracle's digit-plane products are numpy float64 matmuls" % size}
 
 
 def main():
@@ -58,11 +67,16 @@ def main():
     ap.add_argument("--cpu-size", type=int, default=4096)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-native", action="store_true")
+    ap.add_argument("--no-shipped", action="store_true", help="skip the OZ_DYNAMIC + heuristic leg")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only and copy-kernel probes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives or sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    # the CPU leg runs first, so that everything after it in the process is GPU work
+    cpu = None if args.no_cpu else cpu_baseline(args.cpu_size, args.phi)
 
     import numpy as np
     import torch
@@ -81,6 +95,7 @@ def main():
     dA, dB, dC0 = g.to_colmajor(A), g.to_colmajor(B), g.to_colmajor(Cin)
     del A, B, Cin
     dC = dC0.clone()
+    st = torch.cuda.current_stream().cuda_stream
 
     mode = {"forced": g.OZ_FORCED_GUARDED, "unguarded": g.OZ_FIXED_UNGUARDED, "dynamic": g.OZ_DYNAMIC,
             "native": g.OZ_NATIVE}[args.mode]
@@ -92,24 +107,69 @@ def main():
     def step():
         gm.run(dA, m, dB, k, dC, m, alpha, beta)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    h.profile_enable(args.steps)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / args.steps
+    def timed(fn, steps, warmup):
+        """(ms per step over exactly `steps` calls, per-call stage times) -- events on torch's current
+        stream, which is the stream every call here is enqueued on."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        h.profile_enable(steps)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps, np.array([h.profile_read(c) for c in range(steps)])
+
+    ms, per_call = timed(step, args.steps, args.warmup)
     res = gm.result()
-    stages = np.array([h.profile_read(c) for c in range(args.steps)]).mean(axis=0)
+    stages = np.median(per_call, axis=0)
     stage_ms = {name: float(v) for name, v in zip(g.STAGE_NAMES, stages)}
     S = res.slices_used
     flops = 2.0 * m * n * k
     value = flops / (ms * 1e-3) * 1e-12
+
+    def time_it(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # ---- what the part sustains: MFMA-only loop and plain streaming kernels -------------------
+    ceilings = None
+    if not args.no_ceilings:
+        from paper_2511_13778_amd import ozprobe as pr
+        wgs, iters = 1024, 20000
+        sink = torch.zeros(wgs * 256, dtype=torch.int32, device="cuda")
+        ops = float(wgs) * 4 * iters * pr.MFMA_OPS_PER_WAVE_ITER
+        gen = torch.Generator(device="cpu").manual_seed(5)
+        rnd = torch.randint(-128, 128, (pr.MFMA_OPERAND_BYTES,), dtype=torch.int8, generator=gen).cuda()
+        const = torch.full((pr.MFMA_OPERAND_BYTES,), 1, dtype=torch.int8, device="cuda")
+        rates = {}
+        for name, buf in (("constant_operands", const), ("random_operands", rnd)):
+            t = time_it(lambda: pr.launch_mfma_i8(st, buf.data_ptr(), sink.data_ptr(), iters, wgs), reps=2)
+            tops = ops / (t * 1e-3) * 1e-12
+            rates[name] = {"TOPS": tops, "implied_clock_GHz": tops * 1e12 / (CU_COUNT * SIMD_PER_CU * INT8_OPS_PER_CLK_SIMD) * 1e-9}
+        nbytes = 1 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        sink8 = torch.zeros(1, dtype=torch.int64, device="cuda")
+        t_copy = time_it(lambda: pr.launch_copy(st, dst.data_ptr(), src.data_ptr(), nbytes), reps=5)
+        t_read = time_it(lambda: pr.launch_read(st, src.data_ptr(), nbytes, sink8.data_ptr()), reps=5)
+        ceilings = {"mfma_i8_only": rates,
+                    "copy_kernel_GBps": 2 * nbytes / (t_copy * 1e-3) * 1e-9,
+                    "read_kernel_GBps": nbytes / (t_read * 1e-3) * 1e-9,
+                    "note": "MFMA-only loop: 1024 workgroups x 4 waves x 16 accumulators, no memory traffic; "
+                            "implied clock = rate / (256 CU x 4 SIMD x 2048 int8 ops per clock); streaming kernels "
+                            "move 1 GiB"}
+        del src, dst, rnd, const, sink
 
     # dominant kernel: the slice-pair INT8 GEMM.  Algorithmic work per launch: S(S+1)/2 pairs of 2mnk.
     pairs = S * (S + 1) // 2
@@ -126,8 +186,15 @@ def main():
         achieved = pairs * flops / (gemm_ms * 1e-3) * 1e-12
         roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel (v_mfma_i32_32x32x32_i8)", "achieved": achieved,
                     "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s", "frac": achieved / INT8_PEAK_TOPS,
-                    "traffic": traffic, "ops_per_launch": pairs * flops, "kernel_ms": gemm_ms,
+                    "traffic": traffic, "traffic_source": "stored rocprofv3 --pmc measurement (profiles/hbm_traffic.json), "
+                                                          "not taken in this run",
+                    "ops_per_launch": pairs * flops, "kernel_ms": gemm_ms,
                     "note": "int8 multiply-accumulate counted as 2 ops; peak is the published dense INT8 rate"}
+        if ceilings:
+            rnd_tops = ceilings["mfma_i8_only"]["random_operands"]["TOPS"]
+            roofline["measured_mfma_only_ceiling"] = rnd_tops
+            roofline["frac_of_measured_ceiling"] = achieved / rnd_tops
+            roofline["implied_clock_GHz_if_mfma_always_busy"] = achieved * 1e12 / (CU_COUNT * SIMD_PER_CU * INT8_OPS_PER_CLK_SIMD) * 1e-9
     mk, kn, mn = float(m) * k, float(k) * n, float(m) * n
     hbm = {}
     if stage_ms["scan"] > 0:
@@ -139,21 +206,12 @@ def main():
         hbm["recompose"] = {"bytes": byts, "GBps": byts / (stage_ms["recompose"] * 1e-3) * 1e-9}
     for v in hbm.values():
         v["frac_of_hbm_peak"] = v["GBps"] / HBM_PEAK_GBS
+        if ceilings:
+            v["frac_of_copy_kernel"] = v["GBps"] / ceilings["copy_kernel_GBps"]
     guard_ms = stage_ms["scan"] + stage_ms["esc"] + stage_ms["verdict"]
 
     native = {}
     if not args.no_native:
-        def time_it(fn, reps=3):
-            fn()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(reps):
-                fn()
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b) / reps
-        st = torch.cuda.current_stream().cuda_stream
         t_own = time_it(lambda: h.native_dgemm(st, "N", "N", m, n, k, alpha, dA.data_ptr(), m, dB.data_ptr(), k,
                                                beta, dC.data_ptr(), m))
         # vendor FP64 GEMM through torch (rocBLAS/hipBLASLt): column-major C = A*B is (B^T)(A^T) row-major
@@ -161,6 +219,29 @@ def main():
         native = {"own_fp64_mfma_ms": t_own, "own_fp64_mfma_tflops": flops / (t_own * 1e-3) * 1e-12,
                   "vendor_fp64_ms": t_vendor, "vendor_fp64_tflops": flops / (t_vendor * 1e-3) * 1e-12,
                   "speedup_vs_own_fp64": t_own / ms, "speedup_vs_vendor_fp64": t_vendor / ms}
+
+    # ---- the call as it ships: OZ_DYNAMIC, run-time heuristic on ------------------------------
+    shipped = None
+    if not args.no_shipped:
+        dopts = g.default_opts()
+        gd = g.Gemm(h, m, n, k, dopts)
+        ms_d, per_call_d = timed(lambda: gd.run(dA, m, dB, k, dC, m, alpha, beta), 5, 2)
+        rd = gd.result()
+        sd = {name: float(v) for name, v in zip(g.STAGE_NAMES, np.median(per_call_d, axis=0))}
+        guard_d = sd["scan"] + sd["esc"] + sd["verdict"]
+        shipped = {"mode": "oz_default_opts: OZ_DYNAMIC target %d, max %d, heuristic %d, tile_slices %d"
+                           % (dopts.target_bits, dopts.max_bits, dopts.heuristic, dopts.tile_slices), "ms": ms_d,
+                   "tflops": flops / (ms_d * 1e-3) * 1e-12, "fallback": rd.fallback, "reason": rd.reason,
+                   "slices_used": rd.slices_used, "slices_min": rd.slices_min, "pair_tiles": rd.pair_tiles,
+                   "esc": rd.esc, "required_bits": rd.required_bits,
+                   "route": ("scan -> ESC -> verdict -> native FP64 GEMM" if rd.fallback and rd.esc >= 0 else
+                             "native FP64 GEMM without a scan (cost model)" if rd.fallback else
+                             "scan -> ESC -> verdict -> slicing -> slice GEMMs -> recomposition"),
+                   "stage_ms": sd, "guard_ms": guard_d, "guard_share_of_runtime": guard_d / ms_d if ms_d > 0 else None}
+        if native:
+            shipped["x_vendor_fp64"] = native["vendor_fp64_ms"] / ms_d
+            shipped["overhead_over_own_fp64_gemm"] = ms_d / native["own_fp64_mfma_ms"] - 1.0
+        del gd
 
     out = {
         "metric": "effective FP64 TFLOP/s (2mnk/t) at 55-bit, m=n=k=8192; speedup vs FP64 DGEMM",
@@ -172,14 +253,18 @@ def main():
                    "slices_used": S, "esc": res.esc, "fallback": res.fallback, "reason": res.reason},
         "roofline": roofline,
         "stage_ms": stage_ms,
+        "stage_ms_statistic": "median over the timed calls",
+        "ms_per_step_median_of_calls": float(np.median(per_call.sum(axis=1))),
         "guard_share_of_runtime": guard_ms / ms if ms > 0 else None,
         "hbm_stages": hbm,
+        "ceilings": ceilings,
         "native_fp64": native,
+        "shipped_default": shipped,
         "paper_context": "paper reports up to 2.3x (GB200) and 13.2x (RTX Pro 6000 Blackwell) over native FP64 "
                          "GEMM at 55 bits on other hardware; no absolute throughput is published",
     }
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_size, args.phi)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     h.close()
     print(json.dumps(out))
 

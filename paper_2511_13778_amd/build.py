@@ -10,6 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboz_mi355x.so")
+PROBE_LIB = os.path.join(HERE, "liboz_probe.so")      # measurement probes: separate from the product library
+PROBE_SOURCES = ["oz_probe.hip"]
 SOURCES = ["oz_api.hip", "oz_scan.hip", "oz_esc.hip", "oz_slice.hip", "oz_gemm_i8.hip",
            "oz_recompose.hip", "oz_dgemm_f64.hip"]
 # packed FP32 instructions are switched off for all device code (known-bad on the test machines)
@@ -34,15 +36,21 @@ def _compile(src: str, extra=()) -> str:
     return obj
 
 
-def build_library(verbose: bool = True, extra=()) -> str:
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+def _link(lib: str, objs) -> None:
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+
+
+def build_library(verbose: bool = True, extra=()) -> str:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + len(PROBE_SOURCES))) as ex:
+        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES + PROBE_SOURCES))
+    _link(LIB, objs[:len(SOURCES)])
+    _link(PROBE_LIB, objs[len(SOURCES):])
     if verbose:
         print("built", LIB)
+        print("built", PROBE_LIB)
     return LIB
 
 
