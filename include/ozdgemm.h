@@ -70,6 +70,13 @@ typedef struct {
                              first evaluated on the host for the smallest slice count any input can
                              get (ESC = 1); if that already loses against FP64 the call runs the
                              native GEMM without scanning A and B: reason 3, esc -1, infnan 0 */
+    int32_t tile_slices;  /* OZ_DYNAMIC only: 1 = every 256 x 256 block of C takes the slice count of its
+                             own ESC, S_T = ceil((target_bits + ESC_T + 2) / 8): the ESC is a property of
+                             a dot product (section "ESC"), and a tighter estimate is what section
+                             "Limitations and Future Directions" asks for.  Operands are still sliced
+                             once, into max S_T planes; a block multiplies the pairs s + t <= S_T - 1.
+                             Fallback decisions stay global (largest ESC); the cost model is fed the
+                             mean pair count per block, rounded up.  0 = one slice count for all of C */
 } oz_opts_t;
 
 /* Decision record, written to DEVICE memory by the verdict kernel. */
@@ -80,13 +87,19 @@ typedef struct {
     int32_t esc;            /* coarsened ESC (clamped to 4096), -1 when not computed */
     int32_t required_bits;  /* target_bits + ESC, 0 when not computed */
     int32_t infnan;         /* 1 when the scan saw an all-ones exponent field */
+    int32_t slices_min;     /* smallest slice count of any 256 x 256 block of C (== slices_used unless
+                               tile_slices); 0 when fallback */
+    int32_t reserved_;      /* 0 */
+    int64_t pair_tiles;     /* slice-pair products of 256 x 256 blocks of C that the call multiplies:
+                               sum over blocks of S_T (S_T + 1) / 2; 0 when fallback */
 } oz_result_t;
 
 /* Cost model of the run-time heuristic (section "Heuristic run time Selection"); integer
  * arithmetic so that host, device and any checker agree bit for bit:
  *   t_emu = fixed_ns + (2mnk / int8_ops_per_ns) * S(S+1)/2
  *           + ((8+S)(mk+kn) + (8S+16)mn) / bytes_per_ns,      t_f64 = 2mnk / fp64_flops_per_ns,
- * emulation is "slower" when t_emu > t_f64. */
+ * emulation is "slower" when t_emu > t_f64.  With tile_slices the factor S(S+1)/2 is replaced by the
+ * mean pair count per 256 x 256 block of C, rounded up; S in the streaming term is the largest S_T. */
 typedef struct {
     int64_t int8_ops_per_ns;
     int64_t fp64_flops_per_ns;
@@ -105,7 +118,8 @@ oz_status_t oz_create(oz_handle_t* handle, int device);
  * not waited for: it only references caller-owned device memory.  OZ_ERR_ARG on NULL. */
 oz_status_t oz_destroy(oz_handle_t handle);
 
-/* Fills *opts with the defaults: OZ_DYNAMIC, target 53, max 200, slices 0, esc_block 0, heuristic 1. */
+/* Fills *opts with the defaults: OZ_DYNAMIC, target 53, max 200, slices 0, esc_block 0, heuristic 1,
+ * tile_slices 1. */
 void oz_default_opts(oz_opts_t* opts);
 
 /* Replaces the heuristic's constants (defaults are calibrated for MI355X). */
@@ -166,10 +180,12 @@ oz_status_t oz_dgemm_strided_batched(oz_handle_t handle, void* stream, char tran
  *   Bs   int8 [S_cap][kp/16][np][16]   slice t of op(B): element (l,j) likewise with j for i
  *   P    int32[nkb][S_cap][np][mp]     anti-diagonal sums sum_{s+t=d} As_s Bs_t^T of k-block kb:
  *                               element (i,j) at ((kb*S_cap + d)*np + j)*mp + i
+ *   tileS int32[np/256][mp/256]  slice count of block (ti, tj) of C at tj*(mp/256) + ti (written only
+ *                               with tile_slices in OZ_DYNAMIC mode)
  * mp, np = m, n rounded up to 256; kp = k rounded up to 128; kblk = k-block length for S_cap. */
 typedef struct {
     int64_t mp, np, kp, s_cap, nkb, kblk;
-    size_t off_eA, off_eB, off_As, off_Bs, off_P, off_record;
+    size_t off_eA, off_eB, off_As, off_Bs, off_P, off_record, off_tileS;
     size_t total_bytes;
 } oz_layout_t;
 

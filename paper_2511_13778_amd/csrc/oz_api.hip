@@ -39,6 +39,7 @@ bool valid_opts(const oz_opts_t& o) {
     if (o.slices < 0 || o.slices > kMaxSlices) return false;
     if (o.esc_block < 0 || o.esc_block > 1024 || o.esc_block % 16 != 0) return false;
     if (o.heuristic != 0 && o.heuristic != 1) return false;
+    if (o.tile_slices != 0 && o.tile_slices != 1) return false;
     return true;
 }
 
@@ -60,7 +61,10 @@ int slice_cap(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, int6
     }
     int s = (o.max_bits + 1 + kHeadroomBits + 7) / 8;
     if (s > kMaxSlices) s = kMaxSlices;
-    if (o.heuristic)   // the cost model is monotone in S: beyond this the verdict is "slower"
+    // One slice count for all of C: the cost model is monotone in S, beyond this the verdict is
+    // "slower".  With per-tile counts the model sees the mean pair count, so a few blocks may take any
+    // count max_bits allows while the call still pays: no tighter cap than max_bits.
+    if (o.heuristic && !o.tile_slices)
         while (s > 1 && emulation_slower(h.hm, s, m, n, k)) --s;
     return s;
 }
@@ -85,6 +89,7 @@ bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, 
     p.G = int((p.k + p.esc_block - 1) / p.esc_block);
     if (p.G < 1) p.G = 1;
     p.num_cu = h.num_cu;
+    p.tile_mode = (o.mode == OZ_DYNAMIC && o.tile_slices) ? 1 : 0;
     return true;
 }
 
@@ -105,6 +110,9 @@ void make_layout(const Problem& p, oz_layout_t& L) {
     L.off_As = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.mp);
     L.off_Bs = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.np);
     L.off_P = off; off = align_up(off + size_t(p.nkb) * p.s_cap * p.np * p.mp * 4);
+    const size_t tiles = size_t(p.mp / kTile) * size_t(p.np / kTile);
+    off = align_up(off + tiles * 4);                 // tile_span (not part of the published layout)
+    L.off_tileS = off; off = align_up(off + tiles * 4);
     L.total_bytes = off;
 }
 
@@ -125,6 +133,8 @@ Workspace bind(void* base, const Problem& p, const oz_layout_t& L) {
     w.As = reinterpret_cast<int8_t*>(b + L.off_As);
     w.Bs = reinterpret_cast<int8_t*>(b + L.off_Bs);
     w.P = reinterpret_cast<int32_t*>(b + L.off_P);
+    w.tile_span = reinterpret_cast<int32_t*>(b + align_up(L.off_P + size_t(p.nkb) * p.s_cap * p.np * p.mp * 4));
+    w.tile_S = reinterpret_cast<int32_t*>(b + L.off_tileS);
     return w;
 }
 
@@ -181,6 +191,7 @@ void oz_default_opts(oz_opts_t* o) {
     o->slices = 0;
     o->esc_block = 0;
     o->heuristic = 1;
+    o->tile_slices = 1;
 }
 
 oz_status_t oz_create(oz_handle_t* handle, int device) {
@@ -278,10 +289,14 @@ oz_status_t oz_native_dgemm(oz_handle_t h, void* stream, char transa, char trans
     return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
 }
 
-oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n, int64_t k,
-                     double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
-                     double* C, int64_t ldc, const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
-                     oz_result_t* result) {
+}  // extern "C"
+
+namespace {
+
+oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                       double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                       double* C, int64_t ldc, const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
+                       oz_result_t* result) {
     bool ta, tb;
     if (!h || !opts || !parse_trans(transa, ta) || !parse_trans(transb, tb)) return OZ_ERR_ARG;
     if (!valid_opts(*opts)) return OZ_ERR_ARG;
@@ -344,6 +359,7 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
     clk.done(0);
     if (guarded) launch_esc(st, w, p);
     clk.done(1);
+    if (p.tile_mode) launch_tile_verdict(st, w, p, *opts);
     launch_verdict(st, w, p, *opts, h->hm, guarded ? 1 : 0, result);
     clk.done(2);
     launch_slice(st, A, a_sr, a_sl, m, p.mp, p, w.eA, w.As, w.rec);
@@ -356,6 +372,18 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
     if (guarded) launch_dgemm_f64(st, w.rec, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
     clk.done(6);
     return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                     double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                     double* C, int64_t ldc, const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
+                     oz_result_t* result) {
+    return dgemm_impl(h, stream, transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, opts, workspace,
+                      workspace_bytes, result);
 }
 
 oz_status_t oz_dgemm_strided_batched(oz_handle_t h, void* stream, char transa, char transb, int64_t m,

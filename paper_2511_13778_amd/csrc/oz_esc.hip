@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256) void esc_encode_kernel(const int16_t* __restri
 __global__ __launch_bounds__(256) void esc_mfma_kernel(const uint4* __restrict__ EU,
                                                        const uint4* __restrict__ EV, int64_t m,
                                                        int64_t n, int64_t mp, int64_t np,
-                                                       int steps, Record* rec) {
+                                                       int steps, Record* rec,
+                                                       int32_t* __restrict__ tile_span) {
     if (rec->infnan) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane & 31, lh = lane >> 5;
@@ -160,9 +161,12 @@ __global__ __launch_bounds__(256) void esc_mfma_kernel(const uint4* __restrict__
         // Below the encodable range (or no candidate at all): the int16 kernel visits every pair,
         // including the ones this tile resolved, so nothing else needs to be recorded here.
         atomicOr(&rec->esc_exact, 1);
-    } else if (-t > *reinterpret_cast<volatile int32_t*>(&rec->span_max)) {
+    } else {
+        // this 128 x 128 block is resolved exactly: its largest span goes to the C block it lies in
+        // (four such blocks per kTile x kTile block) and to the global maximum
+        atomicMax(&tile_span[(blockIdx.y >> 1) * (mp / kTile) + (blockIdx.x >> 1)], -t);
         // a stale read only costs a redundant atomic; the maximum is monotone
-        atomicMax(&rec->span_max, -t);
+        if (-t > *reinterpret_cast<volatile int32_t*>(&rec->span_max)) atomicMax(&rec->span_max, -t);
     }
 }
 
@@ -177,7 +181,8 @@ __global__ __launch_bounds__(256) void esc_kernel(const int16_t* __restrict__ U,
                                                   const int16_t* __restrict__ V,
                                                   const int32_t* __restrict__ eA,
                                                   const int32_t* __restrict__ eB, int64_t mp,
-                                                  int64_t np, int H2, Record* rec) {
+                                                  int64_t np, int H2, Record* rec,
+                                                  int32_t* __restrict__ tile_span) {
     __shared__ short8_t Ut[kEscHChunk][kEscTile / 8];
     __shared__ short8_t Vt[kEscHChunk][kEscTile / 8];
     // Inf/NaN already forces the native path; otherwise run only for what the MFMA kernel left open
@@ -247,18 +252,53 @@ __global__ __launch_bounds__(256) void esc_kernel(const int16_t* __restrict__ U,
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) best = max(best, __shfl_xor(best, off));
-    // the maximum is monotone: a stale read only costs a redundant atomic
-    if ((threadIdx.x & 63) == 0 && best > *reinterpret_cast<volatile int32_t*>(&rec->span_max))
-        atomicMax(&rec->span_max, best);
+    if ((threadIdx.x & 63) == 0) {
+        // this kernel visits every pair, so its block maxima complete the per-block table as well
+        // (kEscTile x kEscTile blocks, four per kTile x kTile block of C)
+        static_assert(kTile == 2 * kEscTile, "four ESC blocks per block of C");
+        atomicMax(&tile_span[(blockIdx.y >> 1) * (mp / kTile) + (blockIdx.x >> 1)], best);
+        // the maximum is monotone: a stale read only costs a redundant atomic
+        if (best > *reinterpret_cast<volatile int32_t*>(&rec->span_max)) atomicMax(&rec->span_max, best);
+    }
+}
+
+// Per-tile mode: slice count of every kTile x kTile block of C from the largest span inside it, plus
+// the two sums the verdict needs (pair products over all blocks, smallest count).
+__global__ __launch_bounds__(256) void tile_verdict_kernel(Record* rec, const int32_t* __restrict__ tile_span,
+                                                           int32_t* __restrict__ tile_S, int64_t tiles,
+                                                           int target_bits) {
+    const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    unsigned long long pairs = 0;
+    int smin = kMaxSlices;
+    if (t < tiles) {
+        const int esc = min(tile_span[t] + 1, kEscCap);
+        int S = (target_bits + esc + 1 + kHeadroomBits + 7) / 8;
+        S = max(1, min(S, kMaxSlices));
+        tile_S[t] = S;
+        pairs = (unsigned long long)(S) * (S + 1) / 2;
+        smin = S;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        pairs += __shfl_xor(pairs, off);
+        smin = min(smin, __shfl_xor(smin, off));
+    }
+    if ((threadIdx.x & 63) == 0 && pairs) {
+        atomicAdd(&rec->pair_acc, pairs);
+        atomicMin(&rec->smin_acc, smin);
+    }
 }
 
 // One thread: slice count and fallback decision from the scan flag and the ESC.
 __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int kind,
-                               int64_t m, int64_t n, int64_t k, int s_cap,
+                               int64_t m, int64_t n, int64_t k, int s_cap, int tile_mode,
                                oz_result_t* user_result) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     oz_result_t r;
     r.fallback = 0; r.reason = 0; r.slices_used = 0; r.esc = -1; r.required_bits = 0; r.infnan = 0;
+    r.slices_min = 0; r.reserved_ = 0; r.pair_tiles = 0;
+    const int64_t tiles = ((m + kTile - 1) / kTile) * ((n + kTile - 1) / kTile);
+    bool per_tile = false;    // the blocks of C carry their own counts (tile_verdict_kernel ran)
     if (kind == 2 || kind == 3) {
         // 2: nothing to multiply (k == 0 or alpha == 0); 3: the host's cost model says that no slice
         // count this call could get beats the native GEMM, so nothing was scanned
@@ -291,10 +331,14 @@ __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int 
             else r.slices_used = s_fixed;
         } else {
             S = max(1, min(S, kMaxSlices));
+            per_tile = tile_mode != 0;
             bool slower = false;
             if (o.heuristic) {
                 const int64_t flops = 2 * m * n * k;
-                const int64_t pairs = int64_t(S) * (S + 1) / 2;
+                // pair products per block of C: S(S+1)/2, or the mean over the blocks, rounded up
+                const int64_t pairs = per_tile ? int64_t((rec->pair_acc + (unsigned long long)(tiles) - 1) /
+                                                         (unsigned long long)(tiles))
+                                               : int64_t(S) * (S + 1) / 2;
                 const int64_t stream = (8 + S) * (m * k + k * n) + (8 * int64_t(S) + 16) * m * n;
                 const int64_t t_emu = hm.fixed_ns + (flops / hm.int8_ops_per_ns) * pairs + stream / hm.bytes_per_ns;
                 const int64_t t_f64 = flops / hm.fp64_flops_per_ns;
@@ -308,6 +352,10 @@ __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int 
     // can select, so this never binds; if it ever did, running with fewer slices would lose bits
     // silently, so the call goes native and says why.
     if (!r.fallback && r.slices_used > s_cap) { r.fallback = 1; r.reason = 2; r.slices_used = 0; }
+    if (!r.fallback && r.slices_used > 0) {
+        r.slices_min = per_tile ? rec->smin_acc : r.slices_used;
+        r.pair_tiles = per_tile ? int64_t(rec->pair_acc) : tiles * (int64_t(r.slices_used) * (r.slices_used + 1) / 2);
+    }
     rec->res = r;
     if (user_result) *user_result = r;
 }
@@ -321,15 +369,21 @@ void launch_esc(hipStream_t st, const Workspace& w, const Problem& p) {
                        w.V, w.eB, p.np, H2, reinterpret_cast<uint4*>(w.EV));
     hipLaunchKernelGGL(esc_mfma_kernel, dim3(unsigned(p.mp / 128), unsigned(p.np / 128)), dim3(256), 0, st,
                        reinterpret_cast<const uint4*>(w.EU), reinterpret_cast<const uint4*>(w.EV), p.m, p.n,
-                       p.mp, p.np, steps, w.rec);
+                       p.mp, p.np, steps, w.rec, w.tile_span);
     hipLaunchKernelGGL(esc_kernel, dim3(unsigned(p.mp / kEscTile), unsigned(p.np / kEscTile)), dim3(256), 0,
-                       st, w.U, w.V, w.eA, w.eB, p.mp, p.np, 2 * p.G, w.rec);
+                       st, w.U, w.V, w.eA, w.eB, p.mp, p.np, 2 * p.G, w.rec, w.tile_span);
+}
+
+void launch_tile_verdict(hipStream_t st, const Workspace& w, const Problem& p, const oz_opts_t& o) {
+    const int64_t tiles = (p.mp / kTile) * (p.np / kTile);
+    hipLaunchKernelGGL(tile_verdict_kernel, dim3(unsigned((tiles + 255) / 256)), dim3(256), 0, st, w.rec,
+                       w.tile_span, w.tile_S, tiles, o.target_bits);
 }
 
 void launch_verdict(hipStream_t st, const Workspace& w, const Problem& p, const oz_opts_t& o,
                     const oz_heuristic_t& hm, int kind, oz_result_t* user_result) {
     hipLaunchKernelGGL(verdict_kernel, dim3(1), dim3(64), 0, st, w.rec, o, hm, kind, p.m, p.n,
-                       p.k, p.s_cap, user_result);
+                       p.k, p.s_cap, p.tile_mode, user_result);
 }
 
 }  // namespace oz

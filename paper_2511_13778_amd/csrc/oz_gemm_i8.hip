@@ -43,6 +43,7 @@ constexpr int kStageBytes = (kBM + kBN) * kBK;   // 32 KB
 constexpr int kGemmLds = kStages * kStageBytes;  // 128 KB
 constexpr int kDmaPerStage = 2 * (kBK / 16);     // DMA instructions per wave per stage (A and B)
 static_assert(kKPad % kBK == 0, "k padding must cover whole K steps");
+static_assert(kBM == kTile && kBN == kTile, "a workgroup tile is one block of C with its own slice count");
 static_assert(kDmaPerStage == 8, "the vmcnt immediates below assume 8 DMA instructions per stage");
 
 constexpr int kRoundTiles = 32;       // workgroups an XCD runs at a time: 32 CUs, one workgroup each
@@ -117,16 +118,21 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                                                       int32_t* __restrict__ P, int64_t mp,
                                                       int64_t np, int64_t kp, int s_cap,
                                                       Record* rec, int full_chip, int zsplit,
-                                                      int tile_begin, int tile_count) {
+                                                      int tile_begin, int tile_count,
+                                                      const int32_t* __restrict__ tile_S) {
     extern __shared__ __align__(16) uint8_t lds[];
     if (rec->res.fallback) return;
-    const int S = rec->res.slices_used;
-    // k-range one int32 accumulator can take with S slices (S*kblk digit products of at most 2^14)
-    const int64_t kblk = ((int64_t(1) << 17) - 1) / S / 256 * 256;
+    const int S_all = rec->res.slices_used;
+    // k-range one int32 accumulator can take with S slices (S*kblk digit products of at most 2^14);
+    // the k-blocks are those of the call's largest slice count, whatever this tile's own count is
+    const int64_t kblk = ((int64_t(1) << 17) - 1) / S_all / 256 * 256;
     const int nkb = int((kp + kblk - 1) / kblk);
 
     int ti, tj, z, xcd, slot, xcd_tiles;
     tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), tile_begin, tile_count, zsplit, ti, tj, z, xcd, slot, xcd_tiles);
+    // slice count of this tile of C: its own (per-tile mode: the first S digit planes of the operands
+    // and the pairs s + t <= S - 1) or the call's
+    const int S = tile_S ? min(tile_S[tj * int(mp / kBM) + ti], S_all) : S_all;
 
     // This workgroup's share of the K steps: part z of zsplit equal parts of the whole k range (one
     // part = everything when the call has enough tiles to fill the chip).  Parts of the same k-block
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     // this: hit rate 49 % instead of 81 %, 10 % more time; at k = 8192 the start of the tile is
     // enough and the extra waits would cost 1 %).  Arrival number q of a workgroup of round r waits
     // for 32*r*steps + (q+1)*members arrivals on the XCD's counter (earlier rounds are full rounds).
-    const int sync_steps = (kp >= kMidSyncMinK && zsplit == 1) ? nkb * S : 1;
+    const int sync_steps = (kp >= kMidSyncMinK && zsplit == 1) ? nkb * S_all : 1;
     const int sync_round = slot / kRoundTiles;
     const int sync_members = min(kRoundTiles, xcd_tiles - sync_round * kRoundTiles);
     const int sync_base = sync_round * kRoundTiles * sync_steps;
@@ -339,6 +345,9 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                 sync_wait = round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members, sync_wait);
         }
     }
+    // a tile with fewer anti-diagonals than the call's largest count still owes the round its
+    // remaining arrivals: the workgroups that walk more of them count on every member
+    if (sync_on && sync_q < sync_steps && threadIdx.x == 0) atomicAdd(&rec->tile_sync[xcd], sync_steps - sync_q);
     // drain the surplus transfers before the workgroup's LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
@@ -388,7 +397,8 @@ void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p) {
             hipLaunchKernelGGL(zero_tiles_kernel, dim3(unsigned(count), unsigned(planes)), dim3(256), 0, st, w.P,
                                p.mp, p.np, nti, ntj, begin, w.rec);
         hipLaunchKernelGGL(gemm_i8_kernel, dim3(unsigned(count) * unsigned(zs)), dim3(256), kGemmLds, st, w.As,
-                           w.Bs, w.P, p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, zs, begin, count);
+                           w.Bs, w.P, p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, zs, begin, count,
+                           p.tile_mode ? w.tile_S : nullptr);
     };
     // Tiles are dealt in rounds of one per CU.  A call with less than three quarters of a round is
     // split along k as a whole; otherwise the full rounds run unsplit and a last round that would

@@ -30,6 +30,8 @@ constexpr int kSumDeadBelow = -10000;
 // ---- tiling constants shared between kernels and the workspace layout --------------------
 constexpr int kRowPad = 256;          // rows of the slice panels are padded to this
 constexpr int kKPad = 128;            // k is padded to this (K tile of the INT8 GEMM)
+constexpr int kTile = 256;            // edge of the blocks of C that can take their own slice count
+                                      // (= the slice GEMM's workgroup tile; kRowPad is a multiple)
 
 // ---- device-resident control record ---------------------------------------------------
 struct Record {
@@ -38,6 +40,9 @@ struct Record {
     int32_t esc_exact;     // set by the MFMA ESC kernel when a pair needs the exact int16 kernel
     int32_t pad_;
     int32_t tile_sync[8];  // per-XCD arrival counters of the slice GEMM's workgroups
+    unsigned long long pair_acc;   // per-tile mode: sum over tiles of S_T(S_T+1)/2 (atomicAdd)
+    int32_t smin_acc;      // per-tile mode: smallest S_T (atomicMin)
+    int32_t pad2_;
     oz_result_t res;       // written by the verdict kernel, read by every later kernel
 };
 
@@ -50,6 +55,7 @@ struct Problem {
     int32_t esc_block;     // b
     int32_t G;             // ceil(k / b)
     int32_t num_cu;        // compute units of the device
+    int32_t tile_mode;     // 1: every kTile x kTile block of C takes its own slice count (OZ_DYNAMIC + tile_slices)
 };
 
 struct Workspace {
@@ -65,6 +71,8 @@ struct Workspace {
     int8_t* As;            // [s_cap][kp/16][mp][16]
     int8_t* Bs;            // [s_cap][kp/16][np][16]
     int32_t* P;            // [nkb][s_cap][np][mp]
+    int32_t* tile_span;    // [np/kTile][mp/kTile] largest coarsened span of the block's dot products (atomicMax)
+    int32_t* tile_S;       // [np/kTile][mp/kTile] slice count of the block (per-tile mode)
 };
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -80,6 +88,8 @@ void launch_scan(hipStream_t st, const double* X, int64_t stride_r, int64_t stri
                  int64_t rows, int64_t rows_p, const Problem& p, int16_t* tab, bool max_first,
                  int32_t* e_out, Record* rec, bool check_infnan);
 void launch_esc(hipStream_t st, const Workspace& w, const Problem& p);
+// per-tile mode: slice count of every block of C from its span, and the sums the verdict needs
+void launch_tile_verdict(hipStream_t st, const Workspace& w, const Problem& p, const oz_opts_t& o);
 // kind: 0 unguarded, 1 guarded, 2 nothing to multiply (record says "emulated, 0 slices"),
 // 3 native by the cost model alone (nothing scanned)
 void launch_verdict(hipStream_t st, const Workspace& w, const Problem& p, const oz_opts_t& o,

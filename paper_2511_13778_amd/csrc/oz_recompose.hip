@@ -22,14 +22,18 @@ __global__ __launch_bounds__(256) void recompose_kernel(const int32_t* __restric
                                                         int64_t mp, int64_t np, int64_t kp, int s_cap,
                                                         double alpha, double beta,
                                                         double* __restrict__ C, int64_t ldc,
-                                                        const Record* rec) {
+                                                        const Record* rec,
+                                                        const int32_t* __restrict__ tile_S, int64_t j_first) {
     if (rec->res.fallback) return;
-    const int S = rec->res.slices_used;
-    const int64_t kblk = ((int64_t(1) << 17) - 1) / S / 256 * 256;
+    const int S_all = rec->res.slices_used;
+    const int64_t kblk = ((int64_t(1) << 17) - 1) / S_all / 256 * 256;   // k-blocks of the call's largest count
     const int nkb = int((kp + kblk - 1) / kblk);
     const int64_t j = blockIdx.y;
     const int64_t i0 = (int64_t(blockIdx.x) * 256 + threadIdx.x) * kRecElemsPerThread;
     if (i0 >= m) return;
+    // per-tile mode: the block of C this element lies in walked only its own anti-diagonals
+    // (four consecutive i never straddle a block: kTile is a multiple of 4)
+    const int S = tile_S ? min(tile_S[((j_first + j) / kTile) * (mp / kTile) + i0 / kTile], S_all) : S_all;
     const int eb = eB[j];
     const int64_t plane = np * mp;
     typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -77,7 +81,8 @@ void launch_recompose(hipStream_t st, const Workspace& w, const Problem& p, doub
     for (int64_t j0 = 0; j0 < p.n; j0 += 65535) {
         const unsigned gy = unsigned(p.n - j0 < 65535 ? p.n - j0 : 65535);
         hipLaunchKernelGGL(recompose_kernel, dim3(gx, gy), dim3(256), 0, st, w.P + j0 * p.mp, w.eA, w.eB + j0,
-                           p.m, p.mp, p.np, p.kp, p.s_cap, alpha, beta, C + j0 * ldc, ldc, w.rec);
+                           p.m, p.mp, p.np, p.kp, p.s_cap, alpha, beta, C + j0 * ldc, ldc, w.rec,
+                           p.tile_mode ? w.tile_S : nullptr, j0);
     }
 }
 

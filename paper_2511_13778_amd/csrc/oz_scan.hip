@@ -39,13 +39,17 @@ struct BlockStat {
 };
 
 // resets the control record and the row / column exponents (targets of atomicMax in the scans)
-__global__ __launch_bounds__(256) void init_kernel(Record* rec, int32_t* eA, int64_t mp, int32_t* eB, int64_t np) {
+__global__ __launch_bounds__(256) void init_kernel(Record* rec, int32_t* eA, int64_t mp, int32_t* eB, int64_t np,
+                                                   int32_t* tile_span, int64_t tiles) {
     const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
     if (t == 0) {
         rec->infnan = 0;
         rec->span_max = 0;
         rec->esc_exact = 0;
+        rec->pair_acc = 0;
+        rec->smin_acc = kMaxSlices;
     }
+    if (t < tiles) tile_span[t] = 0;
     if (t < 8) {
         rec->tile_sync[t] = 0;
     }
@@ -124,8 +128,11 @@ __global__ __launch_bounds__(256) void scan_k_contig_kernel(
 }
 
 void launch_init(hipStream_t st, const Workspace& w, const Problem& p) {
-    const int64_t nmax = p.mp > p.np ? p.mp : p.np;
-    hipLaunchKernelGGL(init_kernel, dim3(unsigned((nmax + 255) / 256)), dim3(256), 0, st, w.rec, w.eA, p.mp, w.eB, p.np);
+    const int64_t tiles = (p.mp / kTile) * (p.np / kTile);
+    int64_t nmax = p.mp > p.np ? p.mp : p.np;
+    if (tiles > nmax) nmax = tiles;
+    hipLaunchKernelGGL(init_kernel, dim3(unsigned((nmax + 255) / 256)), dim3(256), 0, st, w.rec, w.eA, p.mp, w.eB, p.np,
+                       w.tile_span, tiles);
 }
 
 void launch_scan(hipStream_t st, const double* X, int64_t stride_r, int64_t stride_l, int64_t rows,

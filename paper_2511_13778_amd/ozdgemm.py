@@ -20,12 +20,17 @@ STATUS = {0: "ok", 1: "invalid argument", 2: "workspace", 3: "device", 4: "hip"}
 
 class oz_opts_t(C.Structure):
     _fields_ = [("mode", C.c_int32), ("target_bits", C.c_int32), ("max_bits", C.c_int32),
-                ("slices", C.c_int32), ("esc_block", C.c_int32), ("heuristic", C.c_int32)]
+                ("slices", C.c_int32), ("esc_block", C.c_int32), ("heuristic", C.c_int32),
+                ("tile_slices", C.c_int32)]
 
 
 class oz_result_t(C.Structure):
     _fields_ = [("fallback", C.c_int32), ("reason", C.c_int32), ("slices_used", C.c_int32),
-                ("esc", C.c_int32), ("required_bits", C.c_int32), ("infnan", C.c_int32)]
+                ("esc", C.c_int32), ("required_bits", C.c_int32), ("infnan", C.c_int32),
+                ("slices_min", C.c_int32), ("reserved_", C.c_int32), ("pair_tiles", C.c_int64)]
+
+
+RESULT_INT32_WORDS = 10     # sizeof(oz_result_t) / 4
 
 
 class oz_heuristic_t(C.Structure):
@@ -38,7 +43,7 @@ class oz_layout_t(C.Structure):
                 ("nkb", C.c_int64), ("kblk", C.c_int64),
                 ("off_eA", C.c_size_t), ("off_eB", C.c_size_t), ("off_As", C.c_size_t),
                 ("off_Bs", C.c_size_t), ("off_P", C.c_size_t), ("off_record", C.c_size_t),
-                ("total_bytes", C.c_size_t)]
+                ("off_tileS", C.c_size_t), ("total_bytes", C.c_size_t)]
 
 
 EXPORTS = ("oz_create", "oz_destroy", "oz_default_opts", "oz_set_heuristic",
@@ -108,8 +113,22 @@ def _check(status: int, what: str):
         raise OzError(status, what)
 
 
-def make_opts(mode=OZ_DYNAMIC, target_bits=53, max_bits=200, slices=0, esc_block=0, heuristic=1) -> oz_opts_t:
-    return oz_opts_t(mode, target_bits, max_bits, slices, esc_block, heuristic)
+def make_opts(mode=OZ_DYNAMIC, target_bits=53, max_bits=200, slices=0, esc_block=0, heuristic=1,
+              tile_slices=0) -> oz_opts_t:
+    return oz_opts_t(mode, target_bits, max_bits, slices, esc_block, heuristic, tile_slices)
+
+
+def default_opts() -> oz_opts_t:
+    """The library's own defaults (oz_default_opts)."""
+    o = oz_opts_t()
+    load_library().oz_default_opts(C.byref(o))
+    return o
+
+
+def result_from_words(words) -> "Result":
+    """oz_result_t from its ten int32 words (little-endian int64 in the last two)."""
+    w = [int(v) for v in words]
+    return Result(w[0], w[1], w[2], w[3], w[4], w[5], w[6], (w[8] & 0xFFFFFFFF) | (w[9] << 32))
 
 
 @dataclass
@@ -120,6 +139,8 @@ class Result:
     esc: int
     required_bits: int
     infnan: int
+    slices_min: int = 0
+    pair_tiles: int = 0
 
 
 class Handle:
@@ -209,7 +230,7 @@ class Gemm:
             raise OzError(1, "oz_dgemm_workspace_bytes")
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device="cuda")
         assert self.ws.data_ptr() % 256 == 0
-        self.result_dev = torch.zeros(6, dtype=torch.int32, device="cuda")
+        self.result_dev = torch.zeros(RESULT_INT32_WORDS, dtype=torch.int32, device="cuda")
         self.L = handle.layout(transa, transb, m, n, k, opts)
 
     def run(self, A, lda, B, ldb, Cm, ldc, alpha=1.0, beta=0.0):
@@ -220,7 +241,15 @@ class Gemm:
                      self.ws_bytes, self.result_dev.data_ptr())
 
     def result(self) -> Result:
-        return Result(*[int(v) for v in self.result_dev.cpu().tolist()])
+        return result_from_words(self.result_dev.cpu().tolist())
+
+    def tile_slice_counts(self):
+        """Slice count of every 256 x 256 block of C, numpy (mp/256) x (np/256), block (ti, tj) at [ti, tj]
+        (meaningful after a call in OZ_DYNAMIC mode with tile_slices)."""
+        import torch
+        L = self.L
+        nti, ntj = L.mp // 256, L.np // 256
+        return self._view(L.off_tileS, nti * ntj * 4, torch.int32).view(ntj, nti).cpu().numpy().T.copy()
 
     # views of the intermediates in the workspace (for parity tests)
     def _view(self, off, nbytes, dtype):

@@ -18,10 +18,10 @@ def lib():
     return g, g.load_library()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "ozdgemm.h")).read()
+def declared_functions(header="ozdgemm.h", prefix="oz_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(oz_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(%s[a-z0-9_]+)\s*\(" % prefix, text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -32,19 +32,37 @@ def test_every_declared_symbol_is_exported(lib):
         assert getattr(dll, name) is not None
 
 
+def test_every_header_has_its_library(lib):
+    # every header under include/ is covered by one of the two symbol checks
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ozdgemm.h", "ozprobe.h"]
+
+
+def test_probe_library_exports_its_header(lib):
+    from paper_2511_13778_amd import ozprobe as p
+    dll = p.load_library()
+    names = declared_functions("ozprobe.h", "ozp_")
+    assert set(names) == set(p.EXPORTS), names
+    for name in names:
+        assert getattr(dll, name) is not None
+    # argument errors are reported without touching a device
+    assert dll.ozp_launch_mfma_i8(None, None, None, 1, 1) == 1
+    assert dll.ozp_launch_copy(None, None, None, 16) == 1
+    assert dll.ozp_launch_read(None, None, 0, None) == 1
+
+
 def test_struct_sizes_match_header(lib):
     g, _ = lib
-    assert C.sizeof(g.oz_opts_t) == 24
-    assert C.sizeof(g.oz_result_t) == 24
+    assert C.sizeof(g.oz_opts_t) == 28
+    assert C.sizeof(g.oz_result_t) == 40 == 4 * g.RESULT_INT32_WORDS
     assert C.sizeof(g.oz_heuristic_t) == 32
-    assert C.sizeof(g.oz_layout_t) == 6 * 8 + 7 * C.sizeof(C.c_size_t)
+    assert C.sizeof(g.oz_layout_t) == 6 * 8 + 8 * C.sizeof(C.c_size_t)
 
 
 def test_host_only_calls(lib):
     g, dll = lib
     o = g.oz_opts_t()
     dll.oz_default_opts(C.byref(o))
-    assert (o.mode, o.target_bits, o.max_bits, o.slices, o.esc_block, o.heuristic) == (0, 53, 200, 0, 0, 1)
+    assert (o.mode, o.target_bits, o.max_bits, o.slices, o.esc_block, o.heuristic, o.tile_slices) == (0, 53, 200, 0, 0, 1, 1)
     assert dll.oz_status_string(0) == b"ok"
     assert b"workspace" in dll.oz_status_string(2)
     # null handle / null pointers are argument errors, not crashes
@@ -56,6 +74,6 @@ def test_host_only_calls(lib):
 
 def test_no_cpu_fallback_in_binding():
     # the product path must not import the oracle
-    for name in ("ozdgemm.py", "build.py", "workloads.py", "__init__.py"):
+    for name in ("ozdgemm.py", "ozprobe.py", "build.py", "workloads.py", "__init__.py"):
         src = open(os.path.join(ROOT, "paper_2511_13778_amd", name)).read()
         assert "oracle" not in src.replace("CPU oracle's tests", ""), name

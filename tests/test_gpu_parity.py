@@ -73,8 +73,9 @@ def check_against_oracle(g, h, A, B, alpha=1.0, beta=0.0, Cin=None, mode="forced
     tr = oz.emulated_dgemm(A, B, alpha, beta, Cin, mode=MODES[mode], target_bits=target_bits,
                            max_bits=max_bits, slices=slices, esc_block=esc_block or oz.DEFAULT_ESC_BLOCK)
     v = tr.verdict
-    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan) == \
-           (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan)
+    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan, res.slices_min,
+            res.pair_tiles) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan, v.slices_min,
+                                v.pair_tiles)
     if not v.fallback:
         S = v.slices_used
         if intermediates:
@@ -233,6 +234,41 @@ def test_grading_test2_guardrails(lib):
     assert res.fallback == 0 and res.slices_used == oz.slices_dynamic(53, 81)
 
 
+def test_grade_a_sweep_uniform01(lib):
+    # Aspect A2 of section "Numerical Accuracy": U(0,1) squares, maximum and average componentwise
+    # relative error |fl(AB) - AB| / (|A||B|) against n, measured against the exact reference (not
+    # against any product of the library) on 1000 sampled entries per matrix.  Grade A: the maximum
+    # stays below f(n)*eps with f at most linear in n (here f = n, eps = 2^-53).  Observed shape, also
+    # asserted: the emulated results (dynamic and forced to 55 bits) carry a few eps whatever n is,
+    # the native FP64 GEMM's average error grows like sqrt(n).
+    g, h = lib
+    eps = 2.0 ** -53
+    stats = {}
+    for nn in (256, 1024):
+        for seed in (1, 2):
+            A, B = wl.uniform_01(nn, nn, nn, seed=100 * nn + seed)
+            pick = np.random.default_rng(seed).choice(nn * nn, 1000, replace=False)
+            idx = [(int(t // nn), int(t % nn)) for t in pick]
+            exact = ex.exact_entries(A, B, idx)
+            den = ex.bound_denominator(A, B, idx)
+            for name, opt in (("dynamic", dict(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0)),
+                              ("forced55", dict(mode=g.OZ_FORCED_GUARDED, max_bits=55)),
+                              ("native", dict(mode=g.OZ_NATIVE))):
+                got, _, res = run_gpu(g, h, A, B, **opt)
+                rel = np.abs(np.array([got[i, j] for i, j in idx]) - exact) / den / eps
+                assert rel.max() <= nn, (name, nn, seed, rel.max())
+                stats.setdefault((name, nn), []).append((rel.max(), rel.mean()))
+                if name != "native":
+                    assert res.fallback == 0
+    mx = {key: max(v[0] for v in val) for key, val in stats.items()}
+    av = {key: float(np.mean([v[1] for v in val])) for key, val in stats.items()}
+    for name in ("dynamic", "forced55"):
+        assert mx[(name, 256)] <= 4.0 and mx[(name, 1024)] <= 4.0, mx       # flat in n, a few eps
+    assert av[("dynamic", 1024)] <= av[("forced55", 1024)] <= av[("native", 1024)], av
+    trend = av[("native", 1024)] / av[("native", 256)]
+    assert 1.3 <= trend <= 3.0, trend                                        # sqrt(4) = 2, not 4
+
+
 def test_adversarial_wide_span_falls_back(lib):
     g, h = lib
     A, B = wl.wide_span(260, 300, 130, seed=7)
@@ -374,6 +410,73 @@ def test_randomized_configurations(lib, seed):
                          pad=int(rng.integers(0, 4)), bound=(mode == "dynamic"))
 
 
+@pytest.mark.parametrize("ta,tb,seed", [("N", "N", 0), ("T", "N", 1), ("N", "T", 2), ("T", "T", 3)])
+def test_per_tile_slice_counts(lib, ta, tb, seed):
+    # OZ_DYNAMIC with tile_slices: a band of difficult rows makes the blocks of C it crosses need more
+    # slices than the rest.  Record (with the pair count), the per-block slice counts, every
+    # anti-diagonal a block walked, and C must equal the oracle's; the bound must hold everywhere.
+    g, h = lib
+    m, n, k = 600, 700, 300 + 40 * seed
+    lo = [10, 300, 560, 250][seed]
+    A, B = wl.wide_rows(m, k, n, seed=90 + seed, row_lo=lo, row_hi=lo + 12, spread=20 + 4 * seed)
+    Cin = np.random.default_rng(seed).standard_normal((m, n))
+    got, gm, res = run_gpu(g, h, A, B, 1.5, 0.5, Cin, ta, tb, pad=seed, mode=g.OZ_DYNAMIC, target_bits=53,
+                           max_bits=200, heuristic=0, tile_slices=1)
+    tr = oz.emulated_dgemm(A, B, 1.5, 0.5, Cin, mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200, per_tile=True)
+    v = tr.verdict
+    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan, res.slices_min,
+            res.pair_tiles) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan, v.slices_min,
+                                v.pair_tiles)
+    whole = oz.verdict(oz.MODE_DYNAMIC, 53, 200, 0, False, v.esc, m, n, k)
+    assert v.slices_min < v.slices_used and v.pair_tiles < whole.pair_tiles       # fewer pair products than one count for all
+    np.testing.assert_array_equal(gm.tile_slice_counts(), tr.S_tile)
+    S = v.slices_used
+    As, Bs = gm.slices(S)
+    np.testing.assert_array_equal(As, tr.As)
+    np.testing.assert_array_equal(Bs, tr.Bs)
+    P = gm.products(S, tr.P.shape[0])
+    for ti in range(tr.S_tile.shape[0]):
+        for tj in range(tr.S_tile.shape[1]):
+            r, c, St = slice(256 * ti, 256 * ti + 256), slice(256 * tj, 256 * tj + 256), int(tr.S_tile[ti, tj])
+            np.testing.assert_array_equal(P[:, :St, r, c], tr.P[:, :St, r, c])
+    np.testing.assert_array_equal(got, tr.C)
+    pick = np.random.default_rng(seed).choice(m * n, 3000, replace=False)
+    idx = [(int(t // n), int(t % n)) for t in pick] + [(i, j) for i in range(lo, lo + 12) for j in range(0, n, 9)]
+    exact = ex.exact_entries(A, B, idx, 1.5, 0.5, Cin)
+    den = ex.bound_denominator(A, B, idx, 1.5, 0.5, Cin)
+    assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
+
+
+def test_per_tile_cost_model_keeps_a_localised_hard_region_emulated(lib):
+    # With one slice count for all of C the cost model sends this input to the native GEMM (the worst
+    # block's count applied everywhere is too slow); with per-block counts the mean pair count decides,
+    # and only the band pays for its bits.  The constants are set so that the shape itself is in range.
+    g, h = lib
+    m = n = 1536
+    k = 512
+    A, B = wl.wide_rows(m, k, n, seed=95, row_lo=700, row_hi=720, spread=60)
+    hm = oz.HeuristicModel(int8_ops_per_ns=2650000, fp64_flops_per_ns=30000, bytes_per_ns=40000, fixed_ns=0)
+    h2 = g.Handle(0)
+    try:
+        h2.set_heuristic(hm.int8_ops_per_ns, hm.fp64_flops_per_ns, hm.bytes_per_ns, hm.fixed_ns)
+        out = {}
+        for tiles in (0, 1):
+            got, gm, res = run_gpu(g, h2, A, B, mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200, heuristic=1,
+                                   tile_slices=tiles)
+            tr = oz.emulated_dgemm(A, B, mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200, heuristic=hm,
+                                   per_tile=bool(tiles))
+            v = tr.verdict
+            assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.slices_min,
+                    res.pair_tiles) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.slices_min,
+                                        v.pair_tiles)
+            if not v.fallback:
+                np.testing.assert_array_equal(got, tr.C)
+            out[tiles] = (v.fallback, v.reason)
+        assert out[0] == (1, oz.REASON_HEURISTIC) and out[1] == (0, oz.REASON_NONE), out
+    finally:
+        h2.close()
+
+
 def test_strided_batched(lib):
     # four problems of one shape in one call: each takes its own decision (slice counts differ, one
     # falls back on a NaN), results and records per problem as from separate oz_dgemm calls
@@ -390,7 +493,7 @@ def test_strided_batched(lib):
     dA = torch.from_numpy(np.stack([a.T.copy() for a in As])).cuda()     # (nb, k, m): column-major m x k each
     dB = torch.from_numpy(np.stack([b_.T.copy() for b_ in Bs])).cuda()
     dC = torch.from_numpy(np.stack([c.T.copy() for c in Cs])).cuda()
-    recs = torch.zeros((nb, 6), dtype=torch.int32, device="cuda")
+    recs = torch.zeros((nb, g.RESULT_INT32_WORDS), dtype=torch.int32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     h.dgemm_strided_batched(st, "N", "N", m, n, k, -1.0, dA.data_ptr(), m, m * k, dB.data_ptr(), k, k * n, 0.5,
                             dC.data_ptr(), m, m * n, nb, opts, ws.data_ptr(), ws_bytes, recs.data_ptr())
@@ -400,7 +503,9 @@ def test_strided_batched(lib):
     for b in range(nb):
         tr = oz.emulated_dgemm(As[b], Bs[b], -1.0, 0.5, Cs[b], mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200)
         v = tr.verdict
-        assert tuple(int(x) for x in recs[b]) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan)
+        r = g.result_from_words(recs[b])
+        assert (r.fallback, r.reason, r.slices_used, r.esc, r.required_bits, r.infnan, r.slices_min, r.pair_tiles) == \
+               (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan, v.slices_min, v.pair_tiles)
         if v.fallback:
             assert np.isnan(got[b].T[7, :]).all()
         else:
