@@ -155,6 +155,26 @@ oz_status_t oz_dgemm(oz_handle_t handle, void* stream, char transa, char transb,
                      const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
                      oz_result_t* result);
 
+/* oz_dgemm for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a
+ * static device array inside the library, OZ_STATIC_SCRATCH_BYTES per GPU (each GPU the library
+ * runs on holds its own copy until the process ends; its address is resolved once per handle in
+ * oz_create).  The call allocates nothing and frees nothing: it only enqueues the same kernels as
+ * oz_dgemm on `stream`.  All other arguments, conventions and the record are those of oz_dgemm.
+ *   - A problem whose oz_dgemm_workspace_bytes(...) exceeds OZ_STATIC_SCRATCH_BYTES is refused
+ *     with OZ_ERR_WORKSPACE before anything is enqueued (256 MiB holds e.g. 2048^3 with 7 slices,
+ *     or 1024^3 in OZ_DYNAMIC with max_bits = 200).
+ *   - The array keeps the previous call's contents; every stage rewrites what it reads, nothing
+ *     is assumed to start at zero.
+ *   - All calls on one GPU, from any handle or thread, share the one array: calls that overlap in
+ *     time on a GPU race.  Order them on one stream (or with events). */
+#define OZ_STATIC_SCRATCH_BYTES (256u << 20)
+oz_status_t oz_dgemm_static(oz_handle_t handle, void* stream, char transa, char transb,
+                            int64_t m, int64_t n, int64_t k, double alpha,
+                            const double* A, int64_t lda, const double* B, int64_t ldb,
+                            double beta, double* C, int64_t ldc,
+                            const oz_opts_t* opts, oz_result_t* result);
+
 /* batch_count independent problems of one shape: problem b uses A + b*stride_a, B + b*stride_b,
  * C + b*stride_c (strides in elements; 0 repeats an operand; the C blocks must not overlap) and
  * writes its own record to results[b] (device array of batch_count records, may be NULL).  Every

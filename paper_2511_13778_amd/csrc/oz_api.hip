@@ -9,9 +9,16 @@
 
 #include "oz_internal.h"
 
+// Workspace of oz_dgemm_static: device memory owned by the library, one copy per GPU that loads
+// it, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address obtained there (per device, in oz_create) is what the
+// kernels are given.
+static __device__ __align__(256) unsigned char scratch[OZ_STATIC_SCRATCH_BYTES];
+
 struct oz_handle {
     int device;
     int num_cu;
+    void* static_ws;      // device address of `scratch` on this handle's device
     oz_heuristic_t hm;
     // stage timing
     int prof_calls;       // calls still to be recorded
@@ -204,6 +211,19 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
     if (!h) return OZ_ERR_ARG;
     h->device = device;
     h->num_cu = prop.multiProcessorCount;
+    {
+        // every GPU holds its own copy of the static workspace at its own address: resolve it with
+        // the handle's device current, then put the caller's device back
+        int prev = -1;
+        h->static_ws = nullptr;
+        bool ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(device) == hipSuccess &&
+                  hipGetSymbolAddress(&h->static_ws, HIP_SYMBOL(scratch)) == hipSuccess && h->static_ws != nullptr;
+        if (prev >= 0 && prev != device) ok = (hipSetDevice(prev) == hipSuccess) && ok;
+        if (!ok) {
+            delete h;
+            return OZ_ERR_HIP;
+        }
+    }
     // measured on MI355X at 8192^3: slice GEMM 2.65 POP/s, native FP64 GEMM 66-72 TFLOP/s (the lower figure, reached at 4096^3, is used), streaming
     // kernels about 4 TB/s, launch overhead of the ten kernels of a call
     h->hm.int8_ops_per_ns = 2650000;
@@ -384,6 +404,17 @@ oz_status_t oz_dgemm(oz_handle_t h, void* stream, char transa, char transb, int6
                      oz_result_t* result) {
     return dgemm_impl(h, stream, transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, opts, workspace,
                       workspace_bytes, result);
+}
+
+// Same call with the library's static device array as the workspace: nothing is allocated, here or
+// in anything this calls (kernel launches and event records only).  A problem whose workspace
+// would not fit the array is refused before anything is enqueued.
+oz_status_t oz_dgemm_static(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n,
+                            int64_t k, double alpha, const double* A, int64_t lda, const double* B, int64_t ldb,
+                            double beta, double* C, int64_t ldc, const oz_opts_t* opts, oz_result_t* result) {
+    if (!h) return OZ_ERR_ARG;
+    return dgemm_impl(h, stream, transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, opts, h->static_ws,
+                      size_t(OZ_STATIC_SCRATCH_BYTES), result);
 }
 
 oz_status_t oz_dgemm_strided_batched(oz_handle_t h, void* stream, char transa, char transb, int64_t m,

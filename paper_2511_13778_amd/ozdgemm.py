@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(HERE, "liboz_mi355x.so")
 
 OZ_DYNAMIC, OZ_FORCED_GUARDED, OZ_FIXED_GUARDED, OZ_FIXED_UNGUARDED, OZ_NATIVE = range(5)
 OZ_NUM_STAGES = 7
+OZ_STATIC_SCRATCH_BYTES = 256 << 20
 STAGE_NAMES = ("scan", "esc", "verdict", "slicing", "slice_gemm_i8", "recompose", "native_dgemm")
 STATUS = {0: "ok", 1: "invalid argument", 2: "workspace", 3: "device", 4: "hip"}
 
@@ -47,7 +48,7 @@ class oz_layout_t(C.Structure):
 
 
 EXPORTS = ("oz_create", "oz_destroy", "oz_default_opts", "oz_set_heuristic",
-           "oz_dgemm_workspace_bytes", "oz_dgemm", "oz_dgemm_strided_batched", "oz_dgemm_layout", "oz_profile_enable",
+           "oz_dgemm_workspace_bytes", "oz_dgemm", "oz_dgemm_static", "oz_dgemm_strided_batched", "oz_dgemm_layout", "oz_profile_enable",
            "oz_profile_read", "oz_native_dgemm", "oz_status_string")
 
 _lib = None
@@ -86,6 +87,8 @@ def load_library() -> C.CDLL:
     lib.oz_dgemm.argtypes = [H, C.c_void_p] + dims + gemm_args + [C.POINTER(oz_opts_t), C.c_void_p,
                                                                     C.c_size_t, C.c_void_p]
     lib.oz_dgemm.restype = C.c_int
+    lib.oz_dgemm_static.argtypes = [H, C.c_void_p] + dims + gemm_args + [C.POINTER(oz_opts_t), C.c_void_p]
+    lib.oz_dgemm_static.restype = C.c_int
     lib.oz_dgemm_strided_batched.argtypes = [H, C.c_void_p] + dims + [
         C.c_double, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_double, C.c_void_p,
         C.c_int64, C.c_int64, C.c_int64, C.POINTER(oz_opts_t), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -182,6 +185,12 @@ class Handle:
         _check(self.lib.oz_dgemm(self._h, stream_ptr, transa.encode(), transb.encode(), m, n, k, alpha,
                                  A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc, C.byref(opts), ws_ptr, ws_bytes,
                                  result_ptr), "oz_dgemm")
+
+    def dgemm_static(self, stream_ptr, transa, transb, m, n, k, alpha, A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc,
+                     opts: oz_opts_t, result_ptr=None):
+        _check(self.lib.oz_dgemm_static(self._h, stream_ptr, transa.encode(), transb.encode(), m, n, k, alpha,
+                                        A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc, C.byref(opts), result_ptr),
+               "oz_dgemm_static")
 
     def dgemm_strided_batched(self, stream_ptr, transa, transb, m, n, k, alpha, A_ptr, lda, stride_a, B_ptr, ldb,
                               stride_b, beta, C_ptr, ldc, stride_c, batch_count, opts: oz_opts_t, ws_ptr, ws_bytes,
