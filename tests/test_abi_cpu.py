@@ -74,6 +74,6 @@ def test_host_only_calls(lib):
 
 def test_no_cpu_fallback_in_binding():
     # the product path must not import the oracle
-    for name in ("ozdgemm.py", "ozprobe.py", "build.py", "workloads.py", "__init__.py"):
+    for name in ("ozdgemm.py", "ozprobe.py", "qr.py", "build.py", "workloads.py", "__init__.py"):
         src = open(os.path.join(ROOT, "paper_2511_13778_amd", name)).read()
         assert "oracle" not in src.replace("CPU oracle's tests", ""), name

@@ -477,6 +477,44 @@ def test_per_tile_cost_model_keeps_a_localised_hard_region_emulated(lib):
         h2.close()
 
 
+def test_blocked_qr_through_oz_dgemm(lib):
+    # Blocked Householder QR (section "Application-Level Integration") with the three products of every
+    # trailing update going through oz_dgemm.  R is unique up to the signs of its rows, and LAPACK's and
+    # the vendor solver's Householder conventions agree, so R is compared with a reference factorisation
+    # (numpy / LAPACK on the host) column by column: |R - R_ref|_ij <= c n 2^-53 ||A(:, j)||_2.  The
+    # emulated runs must be as close to the reference as the run on the native FP64 GEMM.
+    g, h = lib
+    from paper_2511_13778_amd.qr import blocked_qr
+    n, b = 1024, 128
+    A = np.random.default_rng(77).standard_normal((n, n))
+    R_ref = np.linalg.qr(A, mode="r")
+    colnorm = np.linalg.norm(A, axis=0)
+    tol = 64.0 * n * 2.0 ** -53
+    errs = {}
+    for name, opts in (("native", g.make_opts(mode=g.OZ_NATIVE)),
+                       ("dynamic", g.make_opts(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0, tile_slices=1)),
+                       ("shipped", g.default_opts())):
+        At = g.to_colmajor(A)
+        tau, rep = blocked_qr(h, At, b, opts)
+        R = np.triu(g.from_colmajor(At))
+        sign = np.sign(np.diag(R)) * np.sign(np.diag(R_ref))
+        err = np.abs(R * sign[:, None] - R_ref) / colnorm[None, :]
+        errs[name] = float(err.max())
+        assert errs[name] <= tol, (name, errs[name], tol)
+        assert rep.panels == n // b and len(rep.records) == 3 * (n // b - 1)
+        hist = rep.histogram()
+        if name == "native":
+            assert hist == {"native:forced": len(rep.records)}
+        if name == "dynamic":          # heuristic off: every product emulated, slice counts from the ESC
+            assert all(r.fallback == 0 and r.slices_used >= 7 and r.esc >= 1 for _, _, _, r in rep.records), hist
+            # each call's verdict is what the oracle derives from the ESC the device reported
+            for mm, nn, kk, r in rep.records:
+                assert r.slices_used == oz.slices_dynamic(53, r.esc) and r.slices_min <= r.slices_used
+        if name == "shipped":          # at this size the cost model sends every product to the native GEMM
+            assert all(r.fallback == 1 and r.reason == oz.REASON_HEURISTIC for _, _, _, r in rep.records), hist
+    assert errs["dynamic"] <= 4.0 * errs["native"] + 1e-16, errs
+
+
 def test_strided_batched(lib):
     # four problems of one shape in one call: each takes its own decision (slice counts differ, one
     # falls back on a NaN), results and records per problem as from separate oz_dgemm calls
