@@ -27,7 +27,8 @@ exact; closed-form ESC of the generalised Test-2 matrices (2b+1); power-of-two s
 invariance; integer matrices reproduce an int64 matmul exactly; exact rational reference.
 Parity unpinned (own choices, only the error bound applies): the run-time heuristic's
 cost model, its constants and its shape-only pre-check, the default block length b, the slice
-cap, the int32 k-block length, the rounding order of the FP64 recomposition.
+cap, the int32 k-block length, the order of the carry-normalised FP64 recomposition beyond seven
+slices (up to seven it is the exact integer rounded once, which is pinned).
 """
 from __future__ import annotations
 
@@ -436,9 +437,11 @@ def slice_rows(A: np.ndarray, eA: np.ndarray, S: int) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 def k_block_length(S: int) -> int:
     """Longest k-range one int32 accumulator can take: |digit product| <= 2^14 and an
-    anti-diagonal sums at most S*k_blk of them, so S*k_blk <= 2^17 - 1; rounded down to a
-    multiple of 256."""
-    return ((1 << 17) - 1) // S // 256 * 256
+    anti-diagonal sums at most S*k_blk of them; the carry that the aggregation of the less
+    significant anti-diagonals brings in (normalised_digits) is below 2^23 in magnitude, so
+    S*k_blk*2^14 + 2^23 <= 2^31 - 1, i.e. S*k_blk <= 2^17 - 2^9 - 1; rounded down to a multiple
+    of 256."""
+    return ((1 << 17) - (1 << 9) - 1) // S // 256 * 256
 
 
 def slice_products(As: np.ndarray, Bs: np.ndarray) -> np.ndarray:
@@ -487,19 +490,51 @@ def slice_products_loops(As: np.ndarray, Bs: np.ndarray) -> np.ndarray:
 # O7  recomposition to FP64 and alpha/beta  (sections "FP64 Emulation on Low-Precision
 #     Units" and "Pre-processing and Safety Checks", second half)
 # --------------------------------------------------------------------------------------
+def normalised_digits(P: np.ndarray):
+    """Aggregates the S anti-diagonal sums of each k-block into one exact integer
+    Z = sum_d P_d * 256^(S-1-d), written in base 256 with balanced digits and a leading word:
+    Z = T0 * 256^(S-1) + sum_{d>=1} lo_d * 256^(S-1-d),  lo_d in [-128, 127].
+
+    Carries run from the least significant anti-diagonal upwards: T = P_d + carry,
+    lo_d = the residue of T modulo 256 that lies in [-128, 127], carry = (T - lo_d) / 256.
+    Balanced digits keep a small Z small in every digit (no borrow ripples to the top), so the
+    floating-point conversion that follows loses nothing to cancellation.  Every T (and T0) is
+    asserted to fit int32: the k-block rule leaves room for the carry.  Returns
+    (T0: nkb x m x n int32, lo: nkb x (S-1) x m x n int8, lo[:, d-1] holding lo_d)."""
+    nkb, S, m, n = P.shape
+    lo = np.zeros((nkb, max(S - 1, 0), m, n), dtype=np.int8)
+    carry = np.zeros((nkb, m, n), dtype=np.int64)
+    for d in range(S - 1, 0, -1):
+        T = P[:, d].astype(np.int64) + carry
+        assert np.abs(T).max(initial=0) < (1 << 31) - 128, "int32 accumulator would overflow"
+        digit = ((T + 128) & 255) - 128
+        lo[:, d - 1] = digit.astype(np.int8)
+        carry = (T - digit) >> 8                         # exact division
+    T0 = P[:, 0].astype(np.int64) + carry
+    assert np.abs(T0).max(initial=0) < (1 << 31), "int32 accumulator would overflow"
+    return T0.astype(np.int32), lo
+
+
 def recompose(P: np.ndarray, eA: np.ndarray, eB: np.ndarray) -> np.ndarray:
     """AB_ij = 2^(eA_i + eB_j + 2H - 12) * sum_kb sum_d 256^-d P[kb,d,i,j].
 
-    Order: k-blocks ascending; inside a k-block Horner from the least significant
-    anti-diagonal, R <- P_d + R * 2^-8 (one rounding per step); block results are added in
-    the unscaled range; the power-of-two scale is applied last, so an Inf can only appear in
-    this terminal conversion."""
+    The partial results of a k-block are aggregated exactly, in integer form
+    (normalised_digits), and converted to FP64 only then, least significant digit first:
+    R <- lo_d + R * 2^-8 for d = S-1 .. 1, then R <- T0 + R * 2^-8.  Up to seven slices the
+    digits below T0 have at most 48 bits, so every step but the last is exact and the k-block's
+    value is the exact integer rounded once; beyond seven, balanced digits keep every partial
+    sum within half a unit of its leading digit, so the roundings stay relative to the value
+    itself.  k-blocks are added in ascending order in the
+    unscaled range; the power-of-two scale is applied last, so an Inf can only appear in this
+    terminal conversion."""
     nkb, S, m, n = P.shape
+    T0, lo = normalised_digits(P)
     R = np.zeros((m, n), dtype=np.float64)
     for kb in range(nkb):
         Rb = np.zeros((m, n), dtype=np.float64)
-        for d in range(S - 1, -1, -1):
-            Rb = P[kb, d].astype(np.float64) + Rb * 2.0 ** -8
+        for d in range(S - 1, 0, -1):
+            Rb = lo[kb, d - 1].astype(np.float64) + Rb * 2.0 ** -8
+        Rb = T0[kb].astype(np.float64) + Rb * 2.0 ** -8
         R = R + Rb
     ea = np.where(eA > NEG_INF_BELOW, eA, 0).astype(np.int64)
     eb = np.where(eB > NEG_INF_BELOW, eB, 0).astype(np.int64)

@@ -12,12 +12,14 @@ from paper_2511_13778_amd import workloads as wl
 
 
 def test_k_block_rule():
-    assert oz.k_block_length(7) == 18688
+    assert oz.k_block_length(7) == 18432
     assert oz.k_block_length(9) == 14336
     for S in range(1, oz.MAX_SLICES + 1):
         kb = oz.k_block_length(S)
         assert kb % 256 == 0 and kb > 0
-        assert S * kb * 128 * 128 < 2 ** 31          # worst anti-diagonal fits int32
+        # worst anti-diagonal plus the largest carry from below fits int32
+        assert S * kb * 128 * 128 + (1 << 23) < 2 ** 31
+        assert S * (kb + 256) * 128 * 128 + (1 << 23) >= 2 ** 31 or S * (kb + 256) > (1 << 17) - (1 << 9) - 1
 
 
 def test_products_match_literal_loops():
@@ -66,6 +68,71 @@ def test_recompose_weights():
     # two k-blocks add in the unscaled range
     P2 = np.concatenate([P, P], axis=0)
     assert oz.recompose(P2, np.array([4]), np.array([-3]))[0, 0] == 2 * got[0, 0]
+
+
+def _exact_Z(P, kb, i, j):
+    S = P.shape[1]
+    return sum(int(P[kb, d, i, j]) * 256 ** (S - 1 - d) for d in range(S))
+
+
+@pytest.mark.parametrize("S", [1, 2, 3, 7, 8, 12, 26])
+def test_normalised_digits_are_the_exact_integer(S):
+    # the carry-normalised digits are balanced base-256 digits of the exact integer sum_d P_d 256^(S-1-d)
+    # under a signed leading word: same value, every lower digit in [-128, 127], and a small
+    # integer stays small in every digit
+    rng = np.random.default_rng(S)
+    bound = ((1 << 17) - (1 << 9) - 1) << 14             # what the k-block rule admits for |P_d|
+    P = rng.integers(-bound, bound + 1, (2, S, 3, 4)).astype(np.int32)
+    P[0, :, 0, 0] = -bound                               # extremes of the admitted range
+    P[0, :, 0, 1] = bound
+    P[1, :, 1, 1] = 0
+    P[1, :, 2, 2] = -1                                   # borrows ripple through every digit
+    T0, lo = oz.normalised_digits(P)
+    assert T0.dtype == np.int32 and lo.dtype == np.int8 and lo.shape == (2, S - 1, 3, 4)
+    if S >= 2:                                           # -1 in every anti-diagonal: no borrow ripple
+        assert T0[1, 2, 2] == -1 and np.all(lo[1, :, 2, 2] == -1)
+    for kb in range(2):
+        for i in range(3):
+            for j in range(4):
+                Z = int(T0[kb, i, j]) * 256 ** (S - 1) + sum(int(lo[kb, d - 1, i, j]) * 256 ** (S - 1 - d) for d in range(1, S))
+                assert Z == _exact_Z(P, kb, i, j)
+
+
+@pytest.mark.parametrize("S", [1, 2, 5, 7])
+def test_recompose_is_the_exact_integer_rounded_once(S):
+    # up to seven slices the FP64 recomposition of a k-block is the correctly rounded value of the
+    # exact integer: no intermediate rounding, whatever the signs of the anti-diagonal sums
+    rng = np.random.default_rng(40 + S)
+    P = rng.integers(-(2 ** 30), 2 ** 30, (1, S, 6, 5)).astype(np.int32)
+    eA, eB = rng.integers(-30, 30, 6), rng.integers(-30, 30, 5)
+    got = oz.recompose(P, eA, eB)
+    for i in range(6):
+        for j in range(5):
+            want = Fraction(_exact_Z(P, 0, i, j)) * Fraction(2) ** (int(eA[i] + eB[j]) + 2 * oz.H - 12 - 8 * (S - 1))
+            assert got[i, j] == float(want)              # Fraction -> float rounds to nearest even
+
+
+def test_recompose_many_slices_stays_within_an_ulp():
+    rng = np.random.default_rng(9)
+    P = rng.integers(-(2 ** 30), 2 ** 30, (3, 12, 4, 4)).astype(np.int32)
+    z = np.zeros(4, dtype=np.int64)
+    got = oz.recompose(P, z, z)
+    for i in range(4):
+        for j in range(4):
+            want = sum(Fraction(_exact_Z(P, kb, i, j)) for kb in range(3)) * Fraction(2) ** (2 * oz.H - 12 - 88)
+            assert abs(Fraction(float(got[i, j])) - want) <= 3 * abs(want) * Fraction(2) ** -52
+
+
+def test_worst_case_digits_with_carry_fit_int32():
+    # every digit at the extreme that makes all products positive, longest k-block: the aggregated
+    # anti-diagonals (sum plus incoming carry) still fit the accumulator
+    for S in (3, 7, 26):
+        k = oz.k_block_length(S)
+        As = np.full((S, 1, k), -128, dtype=np.int8)
+        Bs = np.full((S, 1, k), -128, dtype=np.int8)
+        P = oz.slice_products(As, Bs)
+        T0, lo = oz.normalised_digits(P)                   # asserts the int32 range internally
+        assert P[0, S - 1, 0, 0] == S * k * 16384
 
 
 def test_fsum_reference_matches_rationals():
