@@ -198,14 +198,18 @@ oz_status_t oz_dgemm_strided_batched(oz_handle_t handle, void* stream, char tran
  *   As   int8 [S_cap][kp/16][mp][16]   slice s of op(A): element (i,l) at
  *                               ((s*(kp/16) + l/16)*mp + i)*16 + l%16; padding is zero
  *   Bs   int8 [S_cap][kp/16][np][16]   slice t of op(B): element (l,j) likewise with j for i
- *   P    int32[nkb][S_cap][np][mp]     anti-diagonal sums sum_{s+t=d} As_s Bs_t^T of k-block kb:
- *                               element (i,j) at ((kb*S_cap + d)*np + j)*mp + i
+ *   T    int32[nkb][np][mp]     leading word of the aggregated anti-diagonal sums of k-block kb: with
+ *                               P_d = sum_{s+t=d} As_s Bs_t^T the exact integer Z = sum_d P_d 256^(S-1-d)
+ *                               is T * 256^(S-1) + sum_{d>=1} L_d 256^(S-1-d); element (i,j) at
+ *                               (kb*np + j)*mp + i
+ *   L    int8 [nkb][S_cap-1][np/4][mp][4]   balanced digit L_d in [-128,127], d >= 1, of element (i,j) at
+ *                               (((kb*(S_cap-1) + d-1)*(np/4) + j/4)*mp + i)*4 + j%4
  *   tileS int32[np/256][mp/256]  slice count of block (ti, tj) of C at tj*(mp/256) + ti (written only
  *                               with tile_slices in OZ_DYNAMIC mode)
  * mp, np = m, n rounded up to 256; kp = k rounded up to 128; kblk = k-block length for S_cap. */
 typedef struct {
     int64_t mp, np, kp, s_cap, nkb, kblk;
-    size_t off_eA, off_eB, off_As, off_Bs, off_P, off_record, off_tileS;
+    size_t off_eA, off_eB, off_As, off_Bs, off_T, off_L, off_record, off_tileS;
     size_t total_bytes;
 } oz_layout_t;
 

@@ -97,6 +97,8 @@ bool make_problem(const oz_handle& h, const oz_opts_t& o, int64_t m, int64_t n, 
     if (p.G < 1) p.G = 1;
     p.num_cu = h.num_cu;
     p.tile_mode = (o.mode == OZ_DYNAMIC && o.tile_slices) ? 1 : 0;
+    const int64_t tiles = (p.mp / kTile) * (p.np / kTile);
+    p.raw_slots = int(tiles < h.num_cu ? tiles : h.num_cu);
     return true;
 }
 
@@ -116,7 +118,10 @@ void make_layout(const Problem& p, oz_layout_t& L) {
     off = align_up(off + enc_rows(p) * p.np * 2);
     L.off_As = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.mp);
     L.off_Bs = off; off = align_up(off + size_t(p.s_cap) * p.kp * p.np);
-    L.off_P = off; off = align_up(off + size_t(p.nkb) * p.s_cap * p.np * p.mp * 4);
+    L.off_T = off; off = align_up(off + size_t(p.nkb) * p.np * p.mp * 4);
+    L.off_L = off; off = align_up(off + size_t(p.nkb) * (p.s_cap - 1) * p.np * p.mp);
+    // raw sums of split tiles (not part of the published layout)
+    off = align_up(off + size_t(p.nkb) * p.s_cap * p.raw_slots * kTile * kTile * 4);
     const size_t tiles = size_t(p.mp / kTile) * size_t(p.np / kTile);
     off = align_up(off + tiles * 4);                 // tile_span (not part of the published layout)
     L.off_tileS = off; off = align_up(off + tiles * 4);
@@ -139,8 +144,11 @@ Workspace bind(void* base, const Problem& p, const oz_layout_t& L) {
     w.EV = reinterpret_cast<uint16_t*>(b + offEV);
     w.As = reinterpret_cast<int8_t*>(b + L.off_As);
     w.Bs = reinterpret_cast<int8_t*>(b + L.off_Bs);
-    w.P = reinterpret_cast<int32_t*>(b + L.off_P);
-    w.tile_span = reinterpret_cast<int32_t*>(b + align_up(L.off_P + size_t(p.nkb) * p.s_cap * p.np * p.mp * 4));
+    w.T = reinterpret_cast<int32_t*>(b + L.off_T);
+    w.L = reinterpret_cast<int8_t*>(b + L.off_L);
+    const size_t off_raw = align_up(L.off_L + size_t(p.nkb) * (p.s_cap - 1) * p.np * p.mp);
+    w.raw = reinterpret_cast<int32_t*>(b + off_raw);
+    w.tile_span = reinterpret_cast<int32_t*>(b + align_up(off_raw + size_t(p.nkb) * p.s_cap * p.raw_slots * kTile * kTile * 4));
     w.tile_S = reinterpret_cast<int32_t*>(b + L.off_tileS);
     return w;
 }

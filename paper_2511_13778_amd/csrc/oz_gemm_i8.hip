@@ -4,11 +4,16 @@
 //  count behind "seven slices rather than eight: 22 % less compute"; section "Pre-processing
 //  and Safety Checks": partial results are aggregated so that accumulators cannot overflow.)
 //
-//   P[kb][d][j][i] = sum_{s+t=d} sum_{l in k-block kb} As[s][i][l] * Bs[t][j][l],   d = 0..S-1
+//   P_d[j][i] = sum_{s+t=d} sum_{l in k-block kb} As[s][i][l] * Bs[t][j][l],   d = 0..S-1
 //
 // One launch covers all S(S+1)/2 pairs: a workgroup owns a 256x256 tile of C and walks the
-// anti-diagonals d; all pairs of one d accumulate into the same int32 registers (their k
-// ranges are simply concatenated), so only S tiles are written per k-block.
+// anti-diagonals d from the least significant (S-1) to the most significant (0); all pairs of one d
+// accumulate into the same int32 registers (their k ranges are simply concatenated).  When an
+// anti-diagonal is complete its sum T is split exactly into a balanced digit (T mod 256 in
+// [-128,127], one byte per element, written out) and a carry (T - digit)/256 that stays in the
+// accumulators as the start value of the next anti-diagonal; the last one (d = 0) is written as an
+// int32 word.  So a k-block leaves the exact integer sum_d P_d 256^(S-1-d) in 4 + (S-1) bytes per
+// element instead of 4S, already aggregated: the FP64 recomposition converts it in one pass.
 //
 // Mapping to gfx950:
 //  * v_mfma_i32_32x32x32_i8; 4 waves per workgroup, each wave a 128x128 sub-tile (4x4 MFMA
@@ -90,7 +95,7 @@ __device__ __forceinline__ void lin_to_tile(int lin, int nti, int ntj, int& ti, 
 // (zsplit > 1) a work unit is (tile, part of the k range); units are ordered part by part, so the
 // units an XCD runs together still are neighbouring tiles of the same k range.
 __device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int tile_begin, int tile_count, int zsplit,
-                                        int& ti, int& tj, int& z, int& xcd, int& slot, int& xcd_tiles) {
+                                        int& ti, int& tj, int& z, int& xcd, int& slot, int& xcd_tiles, int& lin) {
     const int total = tile_count * zsplit;
     xcd = bid & 7;
     slot = bid >> 3;
@@ -98,7 +103,8 @@ __device__ __forceinline__ void tile_of(int bid, int nti, int ntj, int tile_begi
     xcd_tiles = per + (xcd < rem ? 1 : 0);
     const int unit = xcd * per + min(xcd, rem) + slot;
     z = unit / tile_count;
-    lin_to_tile(tile_begin + unit - z * tile_count, nti, ntj, ti, tj);
+    lin = tile_begin + unit - z * tile_count;
+    lin_to_tile(lin, nti, ntj, ti, tj);
 }
 
 // 64 lanes x 16 B from global memory into LDS: lane l's 16 bytes land at lds_addr + LDS_IMM + 16*l.
@@ -113,10 +119,26 @@ __device__ __forceinline__ void dma16(const uint8_t* gbase, uint32_t lane_off, u
                  :: "s"(lds_addr), "v"(lane_off), "s"(gbase), "n"(LDS_IMM) : "memory", "scc");
 }
 
+// One dword per lane to a wave-uniform base (scalar register pair) plus a 32-bit per-lane byte offset.
+// Written as assembly so that the address stays in this form: left to itself the compiler builds a
+// 64-bit per-lane address for each of the several hundred stores of an epilogue, hoists them out of
+// the anti-diagonal loop and spills them.
+// The s_nop covers the five wait states the hardware needs between a vector-ALU write of a scalar
+// register (a register-allocator reload with v_readlane, say) and a memory instruction that reads
+// it as its base: inside an asm block the compiler does not insert them itself, and a store issued
+// too early takes the stale register value as its address.
+__device__ __forceinline__ void store_lane_dword(void* uniform_base, uint32_t lane_byte_off, uint32_t data) {
+    asm volatile("s_nop 4\n\tglobal_store_dword %0, %1, %2"
+                 :: "v"(lane_byte_off), "v"(data), "s"(uniform_base) : "memory");
+}
+
+// SPLIT: the launch splits the k range of its tiles over several workgroups (zsplit > 1)
+template <bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__ As,
                                                       const int8_t* __restrict__ Bs,
-                                                      int32_t* __restrict__ P, int64_t mp,
-                                                      int64_t np, int64_t kp, int s_cap,
+                                                      int32_t* __restrict__ T, int8_t* __restrict__ L,
+                                                      int32_t* __restrict__ raw, int raw_slots,
+                                                      int64_t mp, int64_t np, int64_t kp, int s_cap,
                                                       Record* rec, int full_chip, int zsplit,
                                                       int tile_begin, int tile_count,
                                                       const int32_t* __restrict__ tile_S) {
@@ -125,19 +147,21 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     const int S_all = rec->res.slices_used;
     // k-range one int32 accumulator can take with S slices (S*kblk digit products of at most 2^14);
     // the k-blocks are those of the call's largest slice count, whatever this tile's own count is
-    const int64_t kblk = ((int64_t(1) << 17) - 1) / S_all / 256 * 256;
+    const int64_t kblk = k_block_length(S_all);
     const int nkb = int((kp + kblk - 1) / kblk);
 
-    int ti, tj, z, xcd, slot, xcd_tiles;
-    tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), tile_begin, tile_count, zsplit, ti, tj, z, xcd, slot, xcd_tiles);
+    int ti, tj, z, xcd, slot, xcd_tiles, unit_tile;   // unit_tile: this tile's position in the tile order
+    tile_of(blockIdx.x, int(mp / kBM), int(np / kBN), tile_begin, tile_count, zsplit, ti, tj, z, xcd, slot, xcd_tiles,
+            unit_tile);
     // slice count of this tile of C: its own (per-tile mode: the first S digit planes of the operands
     // and the pairs s + t <= S - 1) or the call's
     const int S = tile_S ? min(tile_S[tj * int(mp / kBM) + ti], S_all) : S_all;
 
     // This workgroup's share of the K steps: part z of zsplit equal parts of the whole k range (one
     // part = everything when the call has enough tiles to fill the chip).  Parts of the same k-block
-    // add into the same int32 plane with integer atomics: exact and order-free, so the planes are
-    // the same as without a split.  The host zeroes P before the launch when zsplit > 1.
+    // add their unaggregated anti-diagonal sums into the tile's slot of the raw buffer with integer
+    // atomics: exact and order-free.  The host zeroes the slots before such a launch and aggregates
+    // them afterwards (aggregate_raw_kernel) into the same T / L form the unsplit tiles write.
     const int kt_total = int(kp / kBK);
     const int kt_first = int(int64_t(kt_total) * z / zsplit);
     const int kt_end = int(int64_t(kt_total) * (z + 1) / zsplit);
@@ -152,7 +176,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     // this: hit rate 49 % instead of 81 %, 10 % more time; at k = 8192 the start of the tile is
     // enough and the extra waits would cost 1 %).  Arrival number q of a workgroup of round r waits
     // for 32*r*steps + (q+1)*members arrivals on the XCD's counter (earlier rounds are full rounds).
-    const int sync_steps = (kp >= kMidSyncMinK && zsplit == 1) ? nkb * S_all : 1;
+    const int sync_steps = (kp >= kMidSyncMinK && !SPLIT) ? nkb * S_all : 1;
     const int sync_round = slot / kRoundTiles;
     const int sync_members = min(kRoundTiles, xcd_tiles - sync_round * kRoundTiles);
     const int sync_base = sync_round * kRoundTiles * sync_steps;
@@ -181,7 +205,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     // (nkb_, nd, ns, nkt) walks the (k-block, anti-diagonal, pair, K step) sequence ahead of the
     // compute, so the prefetch runs across pair and anti-diagonal boundaries without a bubble.
     // After the last tile it stays put: the surplus transfers land in stages nobody reads again.
-    int nkb_ = kb_first, nd = 0, ns = 0, nkt = 0;
+    int nkb_ = kb_first, nd = S - 1, ns = 0, nkt = 0;
     int nxt_ktc = kt_count(kb_first);
     int issue_stage = 0;
     const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) uint8_t*)lds));
@@ -201,7 +225,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
     // pointers advance by one K step per tile; only when the pair changes are they recomputed from
     // the iterator (once per k-block length, outside the common path).
     const uint8_t* pa = gA + int64_t(kt_first) * (kBK / 16) * mp * 16;
-    const uint8_t* pb = gB + int64_t(kt_first) * (kBK / 16) * np * 16;
+    const uint8_t* pb = gB + int64_t(S - 1) * (kp * np) + int64_t(kt_first) * (kBK / 16) * np * 16;   // pair (0, S-1)
     const int64_t stepA = int64_t(kBK) * mp, stepB = int64_t(kBK) * np;   // bytes per K step
     uint32_t la;
 #define OZ_TILE_ADDR()                                                                           \
@@ -227,8 +251,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
             nkt = 0;                                                                             \
             if (++ns > nd) {                                                                     \
                 ns = 0;                                                                          \
-                if (++nd == S) {                                                                 \
-                    nd = 0;                                                                      \
+                if (--nd < 0) {                                                                  \
+                    nd = S - 1;                                                                  \
                     if (++nkb_ > kb_last) nkb_ = kb_last;                                        \
                     nxt_ktc = kt_count(nkb_);                                                    \
                 }                                                                                \
@@ -276,7 +300,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 
     for (int kb = kb_first; kb <= kb_last; ++kb) {
         const int ktc = kt_count(kb);
-        for (int d = 0; d < S; ++d) {
+        for (int d = S - 1; d >= 0; --d) {
             const int n_iter = (d + 1) * ktc;
             for (int it = 0; it < n_iter; ++it) {
                 // invariant here: transfers of the next three tiles are in flight (24 per wave);
@@ -324,25 +348,78 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
                 stage = next_stage;
             }
 
-            // anti-diagonal d of k-block kb is complete: write the tile and restart from zero.
+            // anti-diagonal d of k-block kb is complete.
             // result register r of MFMA tile (fj, fi): j = fj*32 + 8*(r/4) + 4*(lane/32) + r%4,
-            // i = fi*32 + lane%32
-            int32_t* dst = P + ((int64_t(kb) * s_cap + d) * np + j0 + wj * 128) * mp + i0 + wi * 128;
+            // i = fi*32 + lane%32.  Every address below is a wave-uniform pointer (scalar arithmetic)
+            // plus one per-lane 32-bit element offset that is the same for all stores of a kind.
+            // the row stride as a value the compiler cannot trace out of this iteration: otherwise the row
+            // addresses of all stores (loop-invariant offsets) are hoisted out of the anti-diagonal loop
+            // and kept alive, several hundred registers' worth, across the MFMA loop
+            int64_t mp_here = mp;
+            asm volatile("" : "+s"(mp_here));
+            if (SPLIT) {
+                // this workgroup holds a part of the k range: add the partial sums into the tile's raw slot
+                int32_t* dst = raw + ((int64_t(kb) * s_cap + d) * raw_slots + (unit_tile - tile_begin)) * (kBM * kBN) +
+                               (wj * 128) * kBM + wi * 128;
+                const uint32_t lane_raw = uint32_t(4 * (lane >> 5)) * kBM + uint32_t(lane & 31);
 #pragma unroll
-            for (int fj = 0; fj < 4; ++fj)
+                for (int fj = 0; fj < 4; ++fj)
 #pragma unroll
-                for (int fi = 0; fi < 4; ++fi) {
+                    for (int fi = 0; fi < 4; ++fi) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int jl = fj * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                        const int il = fi * 32 + (lane & 31);
-                        if (zsplit > 1) atomicAdd(&dst[int64_t(jl) * mp + il], acc[fj][fi][r]);
-                        else dst[int64_t(jl) * mp + il] = acc[fj][fi][r];
+                        for (int r = 0; r < 16; ++r)
+                            atomicAdd(dst + ((fj * 32 + 8 * (r >> 2) + (r & 3)) * kBM + fi * 32) + lane_raw, acc[fj][fi][r]);
+                        acc[fj][fi] = zero;
                     }
-                    acc[fj][fi] = zero;
-                }
+            } else if (d > 0) {
+                // balanced digit out (the low byte of T is its two's-complement form), carry stays: four
+                // consecutive j of one i make a dword, so the lanes of a half-wave write 128 contiguous bytes
+                uint32_t* dst = reinterpret_cast<uint32_t*>(L) +
+                                ((int64_t(kb) * (s_cap - 1) + (d - 1)) * (np / 4) + (j0 + wj * 128) / 4) * mp + i0 + wi * 128;
+                const uint32_t lane_L = (uint32_t(lane >> 5) * uint32_t(mp) + uint32_t(lane & 31)) * 4u;   // bytes
+                const v4i zero4 = {0, 0, 0, 0};
+#pragma unroll
+                for (int fj = 0; fj < 4; ++fj)
+#pragma unroll
+                    for (int fi = 0; fi < 4; ++fi) {
+                        const v16i t = acc[fj][fi];
+                        v16i carry;
+#pragma unroll
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const uint32_t w = (uint32_t(t[4 * rq]) & 255u) | ((uint32_t(t[4 * rq + 1]) & 255u) << 8) |
+                                               ((uint32_t(t[4 * rq + 2]) & 255u) << 16) | (uint32_t(t[4 * rq + 3]) << 24);
+                            store_lane_dword(dst + (int64_t(fj * 8 + 2 * rq) * mp_here + fi * 32), lane_L, w);
+                        }
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) carry[r] = (t[r] + 128) >> 8;
+                        // The carries go back into the accumulator tile as the result of a matrix instruction
+                        // with zero operands (0*0 + carry).  Written by the vector ALU instead, the tile
+                        // would be kept in the ordinary vector registers by the register allocator, and
+                        // sixteen such tiles do not fit there beside the loop's own registers.
+                        acc[fj][fi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, carry, 0, 0, 0);
+                    }
+            } else {
+                // the leading word; the next k-block starts from zero
+                int32_t* dst = T + (int64_t(kb) * np + j0 + wj * 128) * mp + i0 + wi * 128;
+                const uint32_t lane_T = (uint32_t(4 * (lane >> 5)) * uint32_t(mp) + uint32_t(lane & 31)) * 4u;   // bytes
+#pragma unroll
+                for (int fj = 0; fj < 4; ++fj)
+#pragma unroll
+                    for (int fi = 0; fi < 4; ++fi) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            store_lane_dword(dst + (int64_t(fj * 32 + 8 * (r >> 2) + (r & 3)) * mp_here + fi * 32), lane_T,
+                                             uint32_t(acc[fj][fi][r]));
+                        }
+                        acc[fj][fi] = zero;
+                    }
+            }
             if (sync_on && sync_q < sync_steps)
                 sync_wait = round_sync(&rec->tile_sync[xcd], sync_base + (++sync_q) * sync_members, sync_wait);
+            // The operand fragments of the next K step were read during the last one, as in every K
+            // step; reading them again here (eight LDS reads per anti-diagonal) ends their lifetime
+            // before the epilogue above, which needs the registers to pass the accumulators through.
+            OZ_READ_FRAGS(fa0, fb0, stage, 0);
         }
     }
     // a tile with fewer anti-diagonals than the call's largest count still owes the round its
@@ -361,44 +438,89 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__
 #undef OZ_READ_A
 #undef OZ_READ_B
 
-// P = 0 on the tiles of a launch whose workgroups add their parts of the k range into it.
-// grid (tiles of the launch, planes); a workgroup clears one 256 x 256 block of one plane.
-__global__ __launch_bounds__(256) void zero_tiles_kernel(int32_t* __restrict__ P, int64_t mp, int64_t np, int nti,
-                                                         int ntj, int tile_begin, const Record* rec) {
+// raw = 0 on the slots of a launch whose workgroups add their parts of the k range into them.
+// grid (tiles of the launch, planes); a workgroup clears one 256 x 256 slot of one plane.
+__global__ __launch_bounds__(256) void zero_raw_kernel(int32_t* __restrict__ raw, int raw_slots, const Record* rec) {
     if (rec->res.fallback) return;
+    int4* base = reinterpret_cast<int4*>(raw + (int64_t(blockIdx.y) * raw_slots + blockIdx.x) * (kBM * kBN));
+    for (int v = threadIdx.x; v < kBM * kBN / 4; v += 256) base[v] = make_int4(0, 0, 0, 0);
+}
+
+// Aggregates the raw anti-diagonal sums of the split tiles of a launch into the T / L form the unsplit
+// tiles write directly: the same integer carry chain, least significant anti-diagonal first.
+// grid (tiles of the launch, k-blocks); thread = one i of the tile, walking j four at a time.
+__global__ __launch_bounds__(256) void aggregate_raw_kernel(const int32_t* __restrict__ raw, int raw_slots,
+                                                            int32_t* __restrict__ T, int8_t* __restrict__ L,
+                                                            int64_t mp, int64_t np, int64_t kp, int s_cap, int nti,
+                                                            int ntj, int tile_begin, const Record* rec,
+                                                            const int32_t* __restrict__ tile_S) {
+    if (rec->res.fallback) return;
+    const int S_all = rec->res.slices_used;
+    const int nkb = int((kp + k_block_length(S_all) - 1) / k_block_length(S_all));
+    const int kb = blockIdx.y;
+    if (kb >= nkb) return;
     int ti, tj;
     lin_to_tile(tile_begin + int(blockIdx.x), nti, ntj, ti, tj);
-    int32_t* base = P + (int64_t(blockIdx.y) * np + int64_t(tj) * kBN) * mp + int64_t(ti) * kBM;
-    const int col = threadIdx.x & 63, row0 = threadIdx.x >> 6;   // 64 int4 per row of the block
-    for (int jj = row0; jj < kBN; jj += 4)
-        reinterpret_cast<int4*>(base + int64_t(jj) * mp)[col] = make_int4(0, 0, 0, 0);
+    const int S = tile_S ? min(tile_S[tj * nti + ti], S_all) : S_all;
+    const int il = threadIdx.x;
+    const int64_t i = int64_t(ti) * kBM + il, j0 = int64_t(tj) * kBN;
+    const int32_t* src = raw + (int64_t(kb) * s_cap * raw_slots + blockIdx.x) * (kBM * kBN) + il;
+    const int64_t plane = int64_t(raw_slots) * (kBM * kBN);
+    for (int jl4 = 0; jl4 < kBN / 4; ++jl4) {
+        int carry[4] = {0, 0, 0, 0};
+        for (int d = S - 1; d >= 1; --d) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int t = src[d * plane + (jl4 * 4 + q) * kBM] + carry[q];
+                w |= (uint32_t(t) & 255u) << (8 * q);
+                carry[q] = (t + 128) >> 8;
+            }
+            reinterpret_cast<uint32_t*>(L)[((int64_t(kb) * (s_cap - 1) + (d - 1)) * (np / 4) + j0 / 4 + jl4) * mp + i] = w;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            T[(int64_t(kb) * np + j0 + jl4 * 4 + q) * mp + i] = src[(jl4 * 4 + q) * kBM] + carry[q];
+    }
 }
 
 void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p) {
     // the attribute is per device and cheap to set; no process-wide cache that a second device would miss
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     const int nti = int(p.mp / kBM), ntj = int(p.np / kBN);
     const int tiles = nti * ntj;
     const int64_t kt_total = p.kp / kBK;
     const int planes = p.nkb * p.s_cap;
+    const int32_t* tile_S = p.tile_mode ? w.tile_S : nullptr;
     // the workgroup-to-XCD reasoning behind the in-step waits holds for the whole chip only
     // (8 XCDs of 32 CUs); a partitioned device runs the same kernel without them
     const int full_chip = p.num_cu == 8 * kRoundTiles ? 1 : 0;
     // k split for `count` tiles that cannot fill the chip: about one workgroup per CU, each part
-    // keeping at least kMinSplitSteps K steps; the parts add into P with integer atomics
+    // keeping at least kMinSplitSteps K steps; the parts add into the raw buffer with integer atomics
     auto split_for = [&](int count) -> int {
         int zs = p.num_cu / count;
         if (zs > kt_total / kMinSplitSteps) zs = int(kt_total / kMinSplitSteps);
+        if (count > p.raw_slots) zs = 1;      // cannot happen: a split launch has fewer tiles than CUs
         return zs < 1 ? 1 : zs;
     };
     auto launch = [&](int begin, int count, int zs) {
         if (zs > 1)
-            hipLaunchKernelGGL(zero_tiles_kernel, dim3(unsigned(count), unsigned(planes)), dim3(256), 0, st, w.P,
-                               p.mp, p.np, nti, ntj, begin, w.rec);
-        hipLaunchKernelGGL(gemm_i8_kernel, dim3(unsigned(count) * unsigned(zs)), dim3(256), kGemmLds, st, w.As,
-                           w.Bs, w.P, p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, zs, begin, count,
-                           p.tile_mode ? w.tile_S : nullptr);
+            hipLaunchKernelGGL(zero_raw_kernel, dim3(unsigned(count), unsigned(planes)), dim3(256), 0, st, w.raw,
+                               p.raw_slots, w.rec);
+        if (zs > 1)
+            hipLaunchKernelGGL(gemm_i8_kernel<true>, dim3(unsigned(count) * unsigned(zs)), dim3(256), kGemmLds, st,
+                               w.As, w.Bs, w.T, w.L, w.raw, p.raw_slots, p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip,
+                               zs, begin, count, tile_S);
+        else
+            hipLaunchKernelGGL(gemm_i8_kernel<false>, dim3(unsigned(count)), dim3(256), kGemmLds, st, w.As, w.Bs,
+                               w.T, w.L, w.raw, p.raw_slots, p.mp, p.np, p.kp, p.s_cap, w.rec, full_chip, 1, begin,
+                               count, tile_S);
+        if (zs > 1)
+            hipLaunchKernelGGL(aggregate_raw_kernel, dim3(unsigned(count), unsigned(p.nkb)), dim3(256), 0, st, w.raw,
+                               p.raw_slots, w.T, w.L, p.mp, p.np, p.kp, p.s_cap, nti, ntj, begin, w.rec, tile_S);
     };
     // Tiles are dealt in rounds of one per CU.  A call with less than three quarters of a round is
     // split along k as a whole; otherwise the full rounds run unsplit and a last round that would

@@ -56,6 +56,7 @@ struct Problem {
     int32_t G;             // ceil(k / b)
     int32_t num_cu;        // compute units of the device
     int32_t tile_mode;     // 1: every kTile x kTile block of C takes its own slice count (OZ_DYNAMIC + tile_slices)
+    int32_t raw_slots;     // tiles the raw buffer holds (a launch splits the k range of fewer tiles than there are CUs)
 };
 
 struct Workspace {
@@ -70,16 +71,24 @@ struct Workspace {
     uint16_t* EV;          // [ceil(2G/32)*4][np][8] BF16 encoding of V relative to eB
     int8_t* As;            // [s_cap][kp/16][mp][16]
     int8_t* Bs;            // [s_cap][kp/16][np][16]
-    int32_t* P;            // [nkb][s_cap][np][mp]
+    // aggregated anti-diagonal sums of a k-block: Z = sum_d P_d 256^(S-1-d) = T * 256^(S-1) + sum_{d>=1} L_d 256^(S-1-d)
+    int32_t* T;            // [nkb][np][mp]                   leading word (anti-diagonal 0 plus the carry from below)
+    int8_t* L;             // [nkb][s_cap-1][np/4][mp][4]     balanced digit of anti-diagonal d >= 1 at plane d-1; four
+                           //                                 consecutive j of one i share a dword
+    int32_t* raw;          // [nkb][s_cap][raw_slots][kTile][kTile]  unaggregated sums of the tiles whose k range is split
+                           //                                 over several workgroups (integer atomics), tile-local [j][i]
     int32_t* tile_span;    // [np/kTile][mp/kTile] largest coarsened span of the block's dot products (atomicMax)
     int32_t* tile_S;       // [np/kTile][mp/kTile] slice count of the block (per-tile mode)
 };
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
-// k-range one int32 accumulator can take: |digit product| <= 2^14 and an anti-diagonal sums at
-// most S*kblk of them; multiple of 256.
-inline int64_t k_block_length(int S) { return ((int64_t(1) << 17) - 1) / S / 256 * 256; }
+// k-range one int32 accumulator can take: |digit product| <= 2^14, an anti-diagonal sums at most
+// S*kblk of them, and the aggregation adds a carry below 2^23 from the less significant
+// anti-diagonals: S*kblk*2^14 + 2^23 <= 2^31 - 1.  Multiple of 256.
+__host__ __device__ inline int64_t k_block_length(int S) {
+    return ((int64_t(1) << 17) - (int64_t(1) << 9) - 1) / S / 256 * 256;
+}
 
 // ---- stage launchers (each only enqueues) --------------------------------------------
 // element (r, l) of a k-by-rows operand is at base[r*stride_r + l*stride_l]

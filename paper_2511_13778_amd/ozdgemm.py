@@ -43,8 +43,8 @@ class oz_layout_t(C.Structure):
     _fields_ = [("mp", C.c_int64), ("np", C.c_int64), ("kp", C.c_int64), ("s_cap", C.c_int64),
                 ("nkb", C.c_int64), ("kblk", C.c_int64),
                 ("off_eA", C.c_size_t), ("off_eB", C.c_size_t), ("off_As", C.c_size_t),
-                ("off_Bs", C.c_size_t), ("off_P", C.c_size_t), ("off_record", C.c_size_t),
-                ("off_tileS", C.c_size_t), ("total_bytes", C.c_size_t)]
+                ("off_Bs", C.c_size_t), ("off_T", C.c_size_t), ("off_L", C.c_size_t),
+                ("off_record", C.c_size_t), ("off_tileS", C.c_size_t), ("total_bytes", C.c_size_t)]
 
 
 EXPORTS = ("oz_create", "oz_destroy", "oz_default_opts", "oz_set_heuristic",
@@ -293,19 +293,30 @@ class Gemm:
             out.append(t.cpu().numpy())
         return out
 
-    def products_sampled(self, S, nkb, rows, cols):
-        """P[:, :, rows, cols] as a numpy int32 array nkb x S x len(rows) x len(cols)."""
+    def _digit_views(self):
         import torch
         L = self.L
-        t = self._view(L.off_P, L.nkb * L.s_cap * L.np * L.mp * 4, torch.int32).view(L.nkb, L.s_cap, L.np, L.mp)
+        T = self._view(L.off_T, L.nkb * L.np * L.mp * 4, torch.int32).view(L.nkb, L.np, L.mp)
+        nd = max(L.s_cap - 1, 0)
+        Lo = self._view(L.off_L, L.nkb * nd * L.np * L.mp, torch.int8).view(L.nkb, nd, L.np // 4, L.mp, 4)
+        return T, Lo
+
+    def digits_sampled(self, S, nkb, rows, cols):
+        """Aggregated anti-diagonal sums restricted to rows x cols: (T nkb x len(rows) x len(cols) int32,
+        lo nkb x (S-1) x len(rows) x len(cols) int8, lo[:, d-1] = digit of anti-diagonal d)."""
+        import torch
+        T, Lo = self._digit_views()
         ri = torch.as_tensor(rows, device="cuda", dtype=torch.long)
         ci = torch.as_tensor(cols, device="cuda", dtype=torch.long)
-        t = t[:nkb, :S].index_select(2, ci).index_select(3, ri)
-        return t.permute(0, 1, 3, 2).cpu().numpy()
+        t = T[:nkb].index_select(1, ci).index_select(2, ri).permute(0, 2, 1)
+        lo = Lo[:nkb, :max(S - 1, 0)].index_select(3, ri).index_select(2, ci // 4)      # nkb, S-1, cols, rows, 4
+        lo = torch.gather(lo, 4, (ci % 4).view(1, 1, -1, 1, 1).expand(lo.shape[0], lo.shape[1], -1, lo.shape[3], 1))
+        return t.cpu().numpy(), lo.squeeze(4).permute(0, 1, 3, 2).cpu().numpy()
 
-    def products(self, S, nkb):
-        """P as numpy int32 nkb x S x m x n."""
-        import torch
+    def digits(self, S, nkb):
+        """Aggregated anti-diagonal sums of the whole product: (T nkb x m x n int32, lo nkb x (S-1) x m x n int8)."""
+        T, Lo = self._digit_views()
         L = self.L
-        t = self._view(L.off_P, L.nkb * L.s_cap * L.np * L.mp * 4, torch.int32).view(L.nkb, L.s_cap, L.np, L.mp)
-        return t[:nkb, :S, :self.n, :self.m].permute(0, 1, 3, 2).cpu().numpy()
+        t = T[:nkb, :self.n, :self.m].permute(0, 2, 1)
+        lo = Lo[:nkb, :max(S - 1, 0)].permute(0, 1, 3, 2, 4).reshape(nkb, max(S - 1, 0), L.mp, L.np)[:, :, :self.m, :self.n]
+        return t.cpu().numpy(), lo.cpu().numpy()

@@ -55,7 +55,7 @@ def test_struct_sizes_match_header(lib):
     assert C.sizeof(g.oz_opts_t) == 28
     assert C.sizeof(g.oz_result_t) == 40 == 4 * g.RESULT_INT32_WORDS
     assert C.sizeof(g.oz_heuristic_t) == 32
-    assert C.sizeof(g.oz_layout_t) == 6 * 8 + 8 * C.sizeof(C.c_size_t)
+    assert C.sizeof(g.oz_layout_t) == 6 * 8 + 9 * C.sizeof(C.c_size_t)
 
 
 def test_host_only_calls(lib):

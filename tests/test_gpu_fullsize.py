@@ -127,18 +127,23 @@ def sampled_parity(g, h, A, B, alpha, beta, Cin, mode, max_bits, esc_name, nsamp
         np.testing.assert_array_equal(gAs, As)
         np.testing.assert_array_equal(gBs, Bs)
         P = oz.slice_products(As, Bs)
-        gP = gm.products_sampled(S, P.shape[0], I, J)
+        # the slice GEMM leaves the anti-diagonal sums of a k-block aggregated: leading word + balanced digits
+        gT, glo = gm.digits_sampled(S, P.shape[0], I, J)
         if S_tile is None:
-            np.testing.assert_array_equal(gP, P)
+            T0, lo = oz.normalised_digits(P)
+            np.testing.assert_array_equal(gT, T0)
+            np.testing.assert_array_equal(glo, lo)
             want = oz.axpby(alpha, oz.recompose(P, eA[I], eB[J]), beta, Csub)
         else:
             # every sampled entry belongs to a block with its own count: it walked the anti-diagonals
-            # below that count only, and is recomposed from those
+            # below that count only, and is aggregated and recomposed from those
             S_el = S_tile[np.ix_(I // oz.TILE, J // oz.TILE)]
             want = np.empty((len(I), len(J)))
             for St in np.unique(S_el):
                 sel = S_el == St
-                np.testing.assert_array_equal(gP[:, :St][:, :, sel], P[:, :St][:, :, sel])
+                T0, lo = oz.normalised_digits(P[:, :St])
+                np.testing.assert_array_equal(gT[:, sel], T0[:, sel])
+                np.testing.assert_array_equal(glo[:, :St - 1][:, :, sel], lo[:, :, sel])
                 want[sel] = oz.axpby(alpha, oz.recompose(P[:, :St], eA[I], eB[J]), beta, Csub)[sel]
         np.testing.assert_array_equal(got, want)
     del gm, dC

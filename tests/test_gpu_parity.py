@@ -85,7 +85,11 @@ def check_against_oracle(g, h, A, B, alpha=1.0, beta=0.0, Cin=None, mode="forced
             As, Bs = gm.slices(S)
             np.testing.assert_array_equal(As, tr.As)
             np.testing.assert_array_equal(Bs, tr.Bs)
-            np.testing.assert_array_equal(gm.products(S, tr.P.shape[0]), tr.P)
+            # the slice GEMM leaves the anti-diagonal sums of a k-block aggregated (leading word + balanced digits)
+            T0, lo = oz.normalised_digits(tr.P)
+            gT, glo = gm.digits(S, tr.P.shape[0])
+            np.testing.assert_array_equal(gT, T0)
+            np.testing.assert_array_equal(glo, lo)
         np.testing.assert_array_equal(got, tr.C)          # same summation order: bit-identical
     if bound:
         idx = [(i, j) for i in range(m) for j in range(n)]
@@ -417,8 +421,8 @@ def test_per_tile_slice_counts(lib, ta, tb, seed):
     # anti-diagonal a block walked, and C must equal the oracle's; the bound must hold everywhere.
     g, h = lib
     m, n, k = 600, 700, 300 + 40 * seed
-    lo = [10, 300, 560, 250][seed]
-    A, B = wl.wide_rows(m, k, n, seed=90 + seed, row_lo=lo, row_hi=lo + 12, spread=20 + 4 * seed)
+    row0 = [10, 300, 560, 250][seed]
+    A, B = wl.wide_rows(m, k, n, seed=90 + seed, row_lo=row0, row_hi=row0 + 12, spread=20 + 4 * seed)
     Cin = np.random.default_rng(seed).standard_normal((m, n))
     got, gm, res = run_gpu(g, h, A, B, 1.5, 0.5, Cin, ta, tb, pad=seed, mode=g.OZ_DYNAMIC, target_bits=53,
                            max_bits=200, heuristic=0, tile_slices=1)
@@ -434,14 +438,16 @@ def test_per_tile_slice_counts(lib, ta, tb, seed):
     As, Bs = gm.slices(S)
     np.testing.assert_array_equal(As, tr.As)
     np.testing.assert_array_equal(Bs, tr.Bs)
-    P = gm.products(S, tr.P.shape[0])
+    gT, glo = gm.digits(S, tr.P.shape[0])
     for ti in range(tr.S_tile.shape[0]):
         for tj in range(tr.S_tile.shape[1]):
             r, c, St = slice(256 * ti, 256 * ti + 256), slice(256 * tj, 256 * tj + 256), int(tr.S_tile[ti, tj])
-            np.testing.assert_array_equal(P[:, :St, r, c], tr.P[:, :St, r, c])
+            T0, lo = oz.normalised_digits(tr.P[:, :St, r, c])          # the block's own anti-diagonals, aggregated
+            np.testing.assert_array_equal(gT[:, r, c], T0)
+            np.testing.assert_array_equal(glo[:, :St - 1, r, c], lo)
     np.testing.assert_array_equal(got, tr.C)
     pick = np.random.default_rng(seed).choice(m * n, 3000, replace=False)
-    idx = [(int(t // n), int(t % n)) for t in pick] + [(i, j) for i in range(lo, lo + 12) for j in range(0, n, 9)]
+    idx = [(int(t // n), int(t % n)) for t in pick] + [(i, j) for i in range(row0, row0 + 12) for j in range(0, n, 9)]
     exact = ex.exact_entries(A, B, idx, 1.5, 0.5, Cin)
     den = ex.bound_denominator(A, B, idx, 1.5, 0.5, Cin)
     assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
