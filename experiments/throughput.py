@@ -97,9 +97,44 @@ def shapes(torch, g, h, reps):
     print("\n".join(lines), flush=True)
 
 
+def localised(torch, g, h, reps):
+    """A localised hard region: 100 rows of A whose dot products need many more bits than the rest
+    (workloads.wide_rows).  One slice count for all of C against per-block counts, both against FP64."""
+    from paper_2511_13778_amd import workloads as wl
+    st = torch.cuda.current_stream().cuda_stream
+    n = 8192
+    lines = ["# m = n = k = %d, +-U(1,2) entries, rows 3000..3099 of A with a %%d-bit exponent span against every third column;"
+             " alpha = 1, beta = 0; %d timed calls per entry" % (n, reps),
+             "spread | mode                      S_max S_min pair products of 256x256 blocks   ms      TFLOP/s  x vendor FP64"]
+    for spread in (24, 40, 60):
+        A, B = wl.wide_rows(n, n, n, seed=11, row_lo=3000, row_hi=3100, spread=spread)
+        dA, dB = g.to_colmajor(A), g.to_colmajor(B)
+        del A, B
+        dC = torch.zeros((n, n), dtype=torch.float64, device="cuda")
+        t_ven = timed(torch, lambda: torch.matmul(dB, dA), 3)
+        for name, opt in (("dynamic, one count", dict(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0, tile_slices=0)),
+                          ("dynamic, per-block counts", dict(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0, tile_slices=1)),
+                          ("as shipped (heuristic on)", None)):
+            gm = g.Gemm(h, n, n, n, g.default_opts() if opt is None else g.make_opts(**opt))
+            fn = lambda: gm.run(dA, n, dB, n, dC, n, 1.0, 0.0)
+            ms = timed(torch, fn, reps)
+            r = gm.result()
+            what = "native (reason %d)" % r.reason if r.fallback else "%-5d %-5d %d" % (r.slices_used, r.slices_min, r.pair_tiles)
+            lines[0] = lines[0]
+            lines.append("%-6d | %-25s %-40s %-7.2f %-8.1f %.2f" % (spread, name, what, ms, 2.0 * n ** 3 / ms * 1e-9, t_ven / ms))
+            del gm
+        del dA, dB, dC
+        torch.cuda.empty_cache()
+    lines[0] = lines[0].replace("%d-bit", "given-bit")
+    with open(os.path.join(OUT, "throughput_localised.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--shapes", action="store_true")
+    ap.add_argument("--localised", action="store_true")
     ap.add_argument("--sizes", default="8192")
     ap.add_argument("--phis", default="0.1,1,2")
     ap.add_argument("--reps", type=int, default=5)
@@ -114,6 +149,10 @@ def main():
     st = torch.cuda.current_stream().cuda_stream
     if args.shapes:
         shapes(torch, g, h, args.reps)
+        h.close()
+        return
+    if args.localised:
+        localised(torch, g, h, args.reps)
         h.close()
         return
     for n in (int(v) for v in args.sizes.split(",")):

@@ -180,9 +180,15 @@ oz_status_t oz_dgemm_static(oz_handle_t handle, void* stream, char transa, char 
  * writes its own record to results[b] (device array of batch_count records, may be NULL).  Every
  * problem goes through the whole decision process on its own, so slice counts and fallbacks may
  * differ inside a batch (the paper's application runs show a distribution of slice counts over
- * the GEMMs of one factorisation: section "Application-Level Integration").  The problems run
- * one after the other on `stream` and share `workspace`, which is sized as for one oz_dgemm call.
+ * the GEMMs of one factorisation: section "Application-Level Integration").
+ * Concurrency follows the workspace: with room for q >= 2 times oz_dgemm_workspace_bytes(...)
+ * (each rounded up to 256 bytes) the problems run q at a time, q <= OZ_BATCH_LANES, on streams the
+ * handle owns, forked from and joined to `stream` with events (so the call still only enqueues,
+ * and everything it enqueued is ordered before later work on `stream`); with room for one they
+ * run one after the other on `stream`.  Stage timing (oz_profile_*) records serial batches only.
+ * Two batched calls on one handle must not overlap in time (they share the handle's streams).
  * batch_count == 0 is a no-op; errors are those of oz_dgemm, checked before anything is enqueued. */
+#define OZ_BATCH_LANES 4
 oz_status_t oz_dgemm_strided_batched(oz_handle_t handle, void* stream, char transa, char transb,
                                      int64_t m, int64_t n, int64_t k, double alpha,
                                      const double* A, int64_t lda, int64_t stride_a,

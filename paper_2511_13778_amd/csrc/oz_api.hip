@@ -19,6 +19,12 @@ struct oz_handle {
     int device;
     int num_cu;
     void* static_ws;      // device address of `scratch` on this handle's device
+    // lanes of oz_dgemm_strided_batched: streams (default priority) and the events that fork them
+    // from, and join them to, the caller's stream; created once in oz_create
+    hipStream_t lane[OZ_BATCH_LANES];
+    hipEvent_t lane_done[OZ_BATCH_LANES];
+    hipEvent_t fork;
+    bool lanes_ok;
     oz_heuristic_t hm;
     // stage timing
     int prof_calls;       // calls still to be recorded
@@ -172,8 +178,8 @@ struct StageClock {
     oz_handle* h;
     hipStream_t st;
     hipEvent_t* ev;
-    StageClock(oz_handle* hh, hipStream_t s) : h(hh), st(s), ev(nullptr) {
-        if (h->prof_calls > 0 && size_t(h->prof_next + 1) * (OZ_NUM_STAGES + 1) <= h->events.size()) {
+    StageClock(oz_handle* hh, hipStream_t s, bool enabled = true) : h(hh), st(s), ev(nullptr) {
+        if (enabled && h->prof_calls > 0 && size_t(h->prof_next + 1) * (OZ_NUM_STAGES + 1) <= h->events.size()) {
             ev = &h->events[size_t(h->prof_next) * (OZ_NUM_STAGES + 1)];
             --h->prof_calls;
             ++h->prof_next;
@@ -232,6 +238,20 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
             return OZ_ERR_HIP;
         }
     }
+    {
+        // side streams for batched calls; a handle without them still works (batches then run serially)
+        int prev = -1;
+        h->lanes_ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(device) == hipSuccess;
+        for (int l = 0; l < OZ_BATCH_LANES; ++l) { h->lane[l] = nullptr; h->lane_done[l] = nullptr; }
+        h->fork = nullptr;
+        if (h->lanes_ok) {
+            h->lanes_ok = hipEventCreateWithFlags(&h->fork, hipEventDisableTiming) == hipSuccess;
+            for (int l = 0; l < OZ_BATCH_LANES && h->lanes_ok; ++l)
+                h->lanes_ok = hipStreamCreateWithFlags(&h->lane[l], hipStreamNonBlocking) == hipSuccess &&
+                              hipEventCreateWithFlags(&h->lane_done[l], hipEventDisableTiming) == hipSuccess;
+        }
+        if (prev >= 0 && prev != device) (void)hipSetDevice(prev);
+    }
     // measured on MI355X at 8192^3: slice GEMM 2.65 POP/s, native FP64 GEMM 66-72 TFLOP/s (the lower figure, reached at 4096^3, is used), streaming
     // kernels about 4 TB/s, launch overhead of the ten kernels of a call
     h->hm.int8_ops_per_ns = 2650000;
@@ -247,6 +267,11 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
 oz_status_t oz_destroy(oz_handle_t h) {
     if (!h) return OZ_ERR_ARG;
     for (hipEvent_t e : h->events) (void)hipEventDestroy(e);
+    for (int l = 0; l < OZ_BATCH_LANES; ++l) {
+        if (h->lane_done[l]) (void)hipEventDestroy(h->lane_done[l]);
+        if (h->lane[l]) (void)hipStreamDestroy(h->lane[l]);
+    }
+    if (h->fork) (void)hipEventDestroy(h->fork);
     delete h;
     return OZ_OK;
 }
@@ -324,7 +349,7 @@ namespace {
 oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n, int64_t k,
                        double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
                        double* C, int64_t ldc, const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
-                       oz_result_t* result) {
+                       oz_result_t* result, bool timed = true) {
     bool ta, tb;
     if (!h || !opts || !parse_trans(transa, ta) || !parse_trans(transb, tb)) return OZ_ERR_ARG;
     if (!valid_opts(*opts)) return OZ_ERR_ARG;
@@ -344,7 +369,7 @@ oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, in
     // every argument has been accepted: from here on the call only enqueues
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Workspace w = bind(workspace, p, L);
-    StageClock clk(h, st);
+    StageClock clk(h, st, timed);
 
     if (k == 0 || alpha == 0.0) {
         // BLAS convention: nothing to multiply
@@ -439,13 +464,40 @@ oz_status_t oz_dgemm_strided_batched(oz_handle_t h, void* stream, char transa, c
     if (!check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
     if (batch_count > 0 && oz_dgemm_workspace_bytes(h, transa, transb, m, n, k, opts) > workspace_bytes)
         return OZ_ERR_WORKSPACE;
-    for (int64_t b = 0; b < batch_count; ++b) {
-        const oz_status_t st = oz_dgemm(h, stream, transa, transb, m, n, k, alpha, A ? A + b * stride_a : A, lda,
-                                        B ? B + b * stride_b : B, ldb, beta, C ? C + b * stride_c : C, ldc, opts,
-                                        workspace, workspace_bytes, results ? results + b : nullptr);
-        if (st != OZ_OK) return st;
+    if (batch_count == 0 || m == 0 || n == 0) return OZ_OK;
+    const size_t need = align_up(oz_dgemm_workspace_bytes(h, transa, transb, m, n, k, opts));
+    // Lanes: as many problems in flight as the workspace has room for (one slice of `need` bytes each),
+    // at most OZ_BATCH_LANES.  One lane = the caller's stream alone, problems one after the other.
+    int lanes = 1;
+    if (h->lanes_ok && need > 0) {
+        const size_t fit = workspace_bytes / need;
+        lanes = int(fit < size_t(OZ_BATCH_LANES) ? fit : size_t(OZ_BATCH_LANES));
+        if (int64_t(lanes) > batch_count) lanes = int(batch_count);
+        if (lanes < 1) lanes = 1;
     }
-    return OZ_OK;
+    hipStream_t user = static_cast<hipStream_t>(stream);
+    if (lanes > 1) {
+        if (!on_handle_device(*h)) return OZ_ERR_DEVICE;
+        if (hipEventRecord(h->fork, user) != hipSuccess) return OZ_ERR_HIP;
+        for (int l = 0; l < lanes; ++l)
+            if (hipStreamWaitEvent(h->lane[l], h->fork, 0) != hipSuccess) return OZ_ERR_HIP;
+    }
+    oz_status_t status = OZ_OK;
+    for (int64_t b = 0; b < batch_count && status == OZ_OK; ++b) {
+        const int l = int(b % lanes);
+        status = dgemm_impl(h, lanes > 1 ? h->lane[l] : user, transa, transb, m, n, k, alpha, A ? A + b * stride_a : A,
+                            lda, B ? B + b * stride_b : B, ldb, beta, C ? C + b * stride_c : C, ldc, opts,
+                            static_cast<uint8_t*>(workspace) + size_t(l) * need, need, results ? results + b : nullptr,
+                            /*timed=*/lanes == 1);
+    }
+    if (lanes > 1) {
+        // always join, also after an error: the caller's stream must not run ahead of what was enqueued
+        for (int l = 0; l < lanes; ++l) {
+            if (hipEventRecord(h->lane_done[l], h->lane[l]) != hipSuccess) status = status == OZ_OK ? OZ_ERR_HIP : status;
+            if (hipStreamWaitEvent(user, h->lane_done[l], 0) != hipSuccess) status = status == OZ_OK ? OZ_ERR_HIP : status;
+        }
+    }
+    return status;
 }
 
 }  // extern "C"

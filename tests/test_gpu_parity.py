@@ -532,17 +532,32 @@ def test_strided_batched(lib):
         As.append(A); Bs.append(B); Cs.append(Cin)
     As[2][7, 11] = np.nan
     opts = g.make_opts(mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200, heuristic=0)
-    ws_bytes = h.workspace_bytes("N", "N", m, n, k, opts)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    one = h.workspace_bytes("N", "N", m, n, k, opts)
+    one = (one + 255) // 256 * 256
     dA = torch.from_numpy(np.stack([a.T.copy() for a in As])).cuda()     # (nb, k, m): column-major m x k each
     dB = torch.from_numpy(np.stack([b_.T.copy() for b_ in Bs])).cuda()
-    dC = torch.from_numpy(np.stack([c.T.copy() for c in Cs])).cuda()
-    recs = torch.zeros((nb, g.RESULT_INT32_WORDS), dtype=torch.int32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
-    h.dgemm_strided_batched(st, "N", "N", m, n, k, -1.0, dA.data_ptr(), m, m * k, dB.data_ptr(), k, k * n, 0.5,
-                            dC.data_ptr(), m, m * n, nb, opts, ws.data_ptr(), ws_bytes, recs.data_ptr())
-    torch.cuda.synchronize()
-    got, recs = dC.cpu().numpy(), recs.cpu().numpy()
+    runs = []
+    # room for one problem: the batch runs serially on the caller's stream; room for three: three lanes
+    # (streams of the handle, forked from and joined to the caller's stream); same results either way
+    for lanes in (1, 3):
+        ws_bytes = one * lanes
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        dC = torch.from_numpy(np.stack([c.T.copy() for c in Cs])).cuda()
+        recs = torch.zeros((nb, g.RESULT_INT32_WORDS), dtype=torch.int32, device="cuda")
+        h.dgemm_strided_batched(st, "N", "N", m, n, k, -1.0, dA.data_ptr(), m, m * k, dB.data_ptr(), k, k * n, 0.5,
+                                dC.data_ptr(), m, m * n, nb, opts, ws.data_ptr(), ws_bytes, recs.data_ptr())
+        # work enqueued afterwards on the caller's stream is ordered behind every lane
+        tail = dC.sum(dim=(1, 2))
+        torch.cuda.synchronize()
+        runs.append((dC.cpu().numpy(), recs.cpu().numpy(), tail.cpu().numpy()))
+    np.testing.assert_array_equal(runs[0][0], runs[1][0])
+    np.testing.assert_array_equal(runs[0][1], runs[1][1])
+    np.testing.assert_array_equal(runs[0][2], runs[1][2])
+    got, recs = runs[1][0], runs[1][1]
+    ws_bytes = one
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    dC = torch.from_numpy(np.stack([c.T.copy() for c in Cs])).cuda()
     seen = set()
     for b in range(nb):
         tr = oz.emulated_dgemm(As[b], Bs[b], -1.0, 0.5, Cs[b], mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200)
