@@ -229,6 +229,26 @@ def test_esc_across_matrix_unit_range(lib, span):
     assert res.esc == span + 1 and res.fallback == 0
 
 
+def test_fixed_guarded_trips_where_its_slices_run_out(lib):
+    # "55 bits" are seven slices, which carry 54 magnitude bits beside the headroom bit: with ESC = 1 the
+    # fixed-and-guarded mode emulates (53 + 1 = 54), with ESC = 2 (required_bits == max_bits == 55) it
+    # must already fall back, exactly where the dynamic rule moves to eight slices
+    g, h = lib
+    rng = np.random.default_rng(3)
+    m, k, n = 40, 96, 50
+    A = rng.uniform(0.5, 1.0, (m, k)) * rng.choice([-1.0, 1.0], (m, k))
+    B = rng.uniform(0.5, 1.0, (k, n)) * rng.choice([-1.0, 1.0], (k, n))
+    _, res, _ = check_against_oracle(g, h, A, B, mode="fixed_guarded", max_bits=55)
+    assert (res.fallback, res.esc, res.required_bits, res.slices_used) == (0, 1, 54, 7)
+    A[7, 1:] *= 0.5            # one dot product whose best term sits one bit below eA + eB
+    B[0, 9] *= 0.5
+    B[2:, 9] *= 0.5
+    _, res, _ = check_against_oracle(g, h, A, B, mode="fixed_guarded", max_bits=55, bound=False)
+    assert (res.fallback, res.reason, res.esc, res.required_bits) == (1, oz.REASON_BITS, 2, 55)
+    _, res, _ = check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200)
+    assert (res.fallback, res.slices_used) == (0, 8)
+
+
 def test_grading_test2_guardrails(lib):
     g, h = lib
     A, B, x = wl.grading_test2(96, 40, seed=2)
@@ -519,6 +539,65 @@ def test_blocked_qr_through_oz_dgemm(lib):
         if name == "shipped":          # at this size the cost model sends every product to the native GEMM
             assert all(r.fallback == 1 and r.reason == oz.REASON_HEURISTIC for _, _, _, r in rep.records), hist
     assert errs["dynamic"] <= 4.0 * errs["native"] + 1e-16, errs
+
+
+def test_native_gemm_with_a_very_large_leading_dimension(lib):
+    # operands cut out of a huge parent matrix: 15 leading dimensions no longer fit a 32-bit byte offset,
+    # so the FP64 kernel must take its 64-bit indexing path (interior tile sizes on purpose)
+    g, h = lib
+    m, n, k = 128, 128, 32
+    ld = 36_000_000
+    rng = np.random.default_rng(12)
+    A, B = rng.standard_normal((m, k)), rng.standard_normal((k, n))
+    dA = torch.zeros(k * ld, dtype=torch.float64, device="cuda")           # column-major m x k, lda = ld
+    dA.view(k, ld)[:, :m] = torch.from_numpy(np.ascontiguousarray(A.T)).cuda()
+    dBt = torch.zeros(k * ld, dtype=torch.float64, device="cuda")          # B^T stored column-major n x k, ldb = ld
+    dBt.view(k, ld)[:, :n] = torch.from_numpy(np.ascontiguousarray(B)).cuda()
+    dC = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    h.native_dgemm(st, "N", "T", m, n, k, 1.0, dA.data_ptr(), ld, dBt.data_ptr(), ld, 0.0, dC.data_ptr(), m)
+    torch.cuda.synchronize()
+    got = g.from_colmajor(dC)
+    idx = [(i, j) for i in range(0, m, 9) for j in range(0, n, 7)]
+    ratio = ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), ex.exact_entries(A, B, idx),
+                            ex.bound_denominator(A, B, idx), k)
+    assert ratio <= 1.0, ratio
+
+
+def test_concurrent_slice_gemms_share_the_chip(lib):
+    # Two problems with more tiles than the chip runs at a time (324 > 256), in two lanes of a batched
+    # call: their slice GEMMs run concurrently, so the workgroups a tile round waits for may never
+    # arrive.  The waits are bounded and only serve cache locality: the results must equal the serial ones.
+    g, h = lib
+    m = n = 4608
+    k = 512
+    nb = 2
+    mats = [wl.lognormal_spread(m, k, n, 0.5, seed=130 + b) for b in range(nb)]
+    opts = g.make_opts(mode=g.OZ_FORCED_GUARDED, max_bits=55)
+    one = (h.workspace_bytes("N", "N", m, n, k, opts) + 255) // 256 * 256
+    dA = torch.from_numpy(np.stack([a.T.copy() for a, _ in mats])).cuda()
+    dB = torch.from_numpy(np.stack([b_.T.copy() for _, b_ in mats])).cuda()
+    st = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for lanes in (1, 2):
+        ws = torch.empty(one * lanes, dtype=torch.uint8, device="cuda")
+        dC = torch.full((nb, n, m), float("nan"), dtype=torch.float64, device="cuda")
+        recs = torch.zeros((nb, g.RESULT_INT32_WORDS), dtype=torch.int32, device="cuda")
+        h.dgemm_strided_batched(st, "N", "N", m, n, k, 1.0, dA.data_ptr(), m, m * k, dB.data_ptr(), k, k * n, 0.0,
+                                dC.data_ptr(), m, m * n, nb, opts, ws.data_ptr(), one * lanes, recs.data_ptr())
+        torch.cuda.synchronize()
+        outs.append(dC)
+        assert all(g.result_from_words(r).slices_used == 7 for r in recs.cpu().tolist())
+    assert torch.equal(outs[0], outs[1])
+    # and the serial result is the oracle's, on sampled rows and columns of the first problem
+    A, B = mats[0]
+    I = np.array([0, 255, 256, 2000, 4607])
+    J = np.array([1, 300, 4351, 4352, 4606])
+    eA, eB = oz.row_exponents(A), oz.col_exponents(B)
+    P = oz.slice_products(oz.slice_rows(A[I], eA[I], 7), oz.slice_rows(np.ascontiguousarray(B[:, J].T), eB[J], 7))
+    want = oz.recompose(P, eA[I], eB[J])
+    got = outs[1][0].index_select(0, torch.as_tensor(J, device="cuda")).index_select(1, torch.as_tensor(I, device="cuda"))
+    np.testing.assert_array_equal(got.cpu().numpy().T, want)
 
 
 def test_strided_batched(lib):
