@@ -634,3 +634,40 @@ def emulated_dgemm(A: np.ndarray, B: np.ndarray, alpha: float = 1.0, beta: float
     if keep:
         return Trace(v, eA, eB, As, Bs, P, out, S_tile)
     return Trace(v, C=out, S_tile=S_tile)
+
+
+# --------------------------------------------------------------------------------------
+# complex product by the 4M method  (section "Conclusion": the emulation, guardrails included,
+# extends to ZGEMM via 4M: four real matrix products on the real and imaginary parts)
+# --------------------------------------------------------------------------------------
+def emulated_zgemm(A: np.ndarray, B: np.ndarray, alpha: complex = 1.0, beta: complex = 0.0,
+                   C: np.ndarray | None = None, **kw):
+    """C = alpha*A*B + beta*C for complex matrices: with A = Ar + i Ai, B = Br + i Bi,
+
+        Pr = Ar Br - Ai Bi,        Pi = Ar Bi + Ai Br,
+
+    each of the four real products one emulated_dgemm call (its own scan, ESC and verdict; keyword
+    arguments are passed through), the second product of each pair accumulating onto the first
+    (alpha = -1 or +1, beta = 1).  Then  C = alpha*(Pr + i Pi) + beta*C  with every real product and
+    sum rounded separately, in the order written below; C is not read when beta == 0.
+    Returns (C, [the four verdicts in the order Ar Br, Ai Bi, Ar Bi, Ai Br])."""
+    A = np.asarray(A, dtype=np.complex128)
+    B = np.asarray(B, dtype=np.complex128)
+    Ar, Ai = np.ascontiguousarray(A.real), np.ascontiguousarray(A.imag)
+    Br, Bi = np.ascontiguousarray(B.real), np.ascontiguousarray(B.imag)
+    kw = dict(kw, keep=False)
+    t1 = emulated_dgemm(Ar, Br, 1.0, 0.0, None, **kw)
+    t2 = emulated_dgemm(Ai, Bi, -1.0, 1.0, t1.C, **kw)
+    t3 = emulated_dgemm(Ar, Bi, 1.0, 0.0, None, **kw)
+    t4 = emulated_dgemm(Ai, Br, 1.0, 1.0, t3.C, **kw)
+    Pr, Pi = t2.C, t4.C
+    ar, ai = np.float64(complex(alpha).real), np.float64(complex(alpha).imag)
+    br, bi = np.float64(complex(beta).real), np.float64(complex(beta).imag)
+    with np.errstate(over="ignore", invalid="ignore"):
+        out_r = ar * Pr - ai * Pi
+        out_i = ar * Pi + ai * Pr
+        if beta != 0.0:
+            Cr, Ci = np.asarray(C).real, np.asarray(C).imag
+            out_r = out_r + (br * Cr - bi * Ci)
+            out_i = out_i + (br * Ci + bi * Cr)
+    return out_r + 1j * out_i, [t1.verdict, t2.verdict, t3.verdict, t4.verdict]

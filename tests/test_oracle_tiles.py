@@ -164,3 +164,74 @@ def test_heuristic_closed_forms_and_monotonicity():
     t_f64 = Fraction(2 * m * n * k, hm.fp64_flops_per_ns)
     assert abs(t_emu - t_f64) > 40                     # the decision is not a rounding accident
     assert hm.emulation_slower(S, m, n, k) == (t_emu > t_f64)
+
+
+# ---- complex product by the 4M method ------------------------------------------------------------
+def _cexact(A, B, alpha, beta, C):
+    """Exact complex alpha*A*B + beta*C as pairs of Fractions."""
+    F = lambda x: Fraction(float(x))
+    m, k = A.shape
+    n = B.shape[1]
+    out = [[None] * n for _ in range(m)]
+    ar, ai, br, bi = F(alpha.real), F(alpha.imag), F(beta.real), F(beta.imag)
+    for i in range(m):
+        for j in range(n):
+            pr = sum((F(A[i, l].real) * F(B[l, j].real) - F(A[i, l].imag) * F(B[l, j].imag) for l in range(k)), Fraction(0))
+            pi = sum((F(A[i, l].real) * F(B[l, j].imag) + F(A[i, l].imag) * F(B[l, j].real) for l in range(k)), Fraction(0))
+            re, im = ar * pr - ai * pi, ar * pi + ai * pr
+            if beta != 0:
+                re += br * F(C[i, j].real) - bi * F(C[i, j].imag)
+                im += br * F(C[i, j].imag) + bi * F(C[i, j].real)
+            out[i][j] = (re, im)
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_zgemm_4m_meets_the_componentwise_bound(seed):
+    # against exact rational arithmetic: real and imaginary part each within (k + 4) 2^-53 of
+    # (|ar| + |ai|) (|Ar| + |Ai|)(|Br| + |Bi|) + (|br| + |bi|) (|Cr| + |Ci|), the bound the four
+    # real products and the final combination add up to; a wrong sign or a swapped part breaks it
+    rng = np.random.default_rng(700 + seed)
+    m, k, n = int(rng.integers(1, 6)), int(rng.integers(1, 40)), int(rng.integers(1, 6))
+    cplx = lambda shape: (rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * np.exp2(rng.integers(-6, 7, shape))
+    A, B, C = cplx((m, k)), cplx((k, n)), cplx((m, n))
+    alpha, beta = complex(1.25, -0.5), (complex(0.5, 2.0) if seed % 2 else 0.0)
+    got, verdicts = oz.emulated_zgemm(A, B, alpha, beta, C, mode=oz.MODE_DYNAMIC, max_bits=200)
+    assert len(verdicts) == 4 and all(v.fallback == 0 for v in verdicts)
+    want = _cexact(A, B, complex(alpha), complex(beta), C)
+    absA, absB = np.abs(A.real) + np.abs(A.imag), np.abs(B.real) + np.abs(B.imag)
+    den = (abs(alpha.real) + abs(alpha.imag)) * (absA @ absB)
+    if beta != 0:
+        den = den + (abs(complex(beta).real) + abs(complex(beta).imag)) * (np.abs(C.real) + np.abs(C.imag))
+    tol = (k + 4) * 2.0 ** -53
+    worst = 0.0
+    for i in range(m):
+        for j in range(n):
+            er = abs(Fraction(float(got[i, j].real)) - want[i][j][0])
+            ei = abs(Fraction(float(got[i, j].imag)) - want[i][j][1])
+            worst = max(worst, float(max(er, ei)) / (tol * den[i, j]))
+    assert worst <= 1.0, worst
+    # negative control: the conjugate product is far outside
+    bad, _ = oz.emulated_zgemm(A, np.conj(B), alpha, beta, C, mode=oz.MODE_DYNAMIC, max_bits=200)
+    if k > 2:
+        assert np.max(np.abs(bad - got)) > 1e-6 * np.max(np.abs(got))
+
+
+def test_zgemm_reduces_to_the_real_product():
+    # purely real operands: the 4M product is the real emulated product, imaginary part exactly zero
+    rng = np.random.default_rng(9)
+    A, B = rng.standard_normal((5, 30)), rng.standard_normal((30, 4))
+    got, verdicts = oz.emulated_zgemm(A + 0j, B + 0j, mode=oz.MODE_DYNAMIC, max_bits=200)
+    real = oz.emulated_dgemm(A, B, mode=oz.MODE_DYNAMIC, max_bits=200)
+    np.testing.assert_array_equal(got.real, real.C)
+    assert np.all(got.imag == 0.0)
+    assert verdicts[0] == real.verdict
+    # i * (real product): multiplying A by i moves the product to the imaginary part, sign included
+    got_i, _ = oz.emulated_zgemm(1j * A, B + 0j, mode=oz.MODE_DYNAMIC, max_bits=200)
+    np.testing.assert_array_equal(got_i.imag, real.C)
+    assert np.all(got_i.real == 0.0)
+    # Inf/NaN in one part sends only the products that touch it to the native path
+    A2 = A + 0j
+    A2[1, 2] = complex(1.0, np.inf)
+    _, v = oz.emulated_zgemm(A2, B + 1j * B, mode=oz.MODE_DYNAMIC, max_bits=200)
+    assert [x.fallback for x in v] == [0, 1, 0, 1] and v[1].reason == oz.REASON_INFNAN
