@@ -197,6 +197,26 @@ oz_status_t oz_dgemm_strided_batched(oz_handle_t handle, void* stream, char tran
                                      int64_t batch_count, const oz_opts_t* opts,
                                      void* workspace, size_t workspace_bytes, oz_result_t* results);
 
+/* Complex product by the 4M method (section "Conclusion": the emulated DGEMM and its guardrails
+ * extend to ZGEMM via 4M): C = alpha * op(A) * op(B) + beta * C with complex matrices stored
+ * interleaved (re, im), column-major, leading dimensions in complex elements; op is 'N', 'T' or
+ * 'C' (conjugate transpose).  A and B are split into real and imaginary parts, the four real
+ * products  Pr = Ar Br - Ai Bi,  Pi = Ar Bi + Ai Br  run through the emulated DGEMM one after the
+ * other on `stream` (each with its own scan, ESC and verdict; the second of each pair accumulates
+ * onto the first), and C = alpha (Pr + i Pi) + beta C is formed with every real product and sum
+ * rounded separately.  alpha, beta: host pointers to (re, im).  C is not read when beta == 0.
+ * results: device array of four records (Ar Br, Ai Bi, Ar Bi, Ai Br) or NULL.  workspace as for
+ * oz_dgemm, at least oz_zgemm_workspace_bytes(...) (planar copies of A and B, the planar product,
+ * one real call's workspace).  k == 0 gives C = beta C.  Errors as oz_dgemm. */
+size_t oz_zgemm_workspace_bytes(oz_handle_t handle, char transa, char transb,
+                                int64_t m, int64_t n, int64_t k, const oz_opts_t* opts);
+oz_status_t oz_zgemm(oz_handle_t handle, void* stream, char transa, char transb,
+                     int64_t m, int64_t n, int64_t k, const double* alpha,
+                     const void* A, int64_t lda, const void* B, int64_t ldb,
+                     const double* beta, void* C, int64_t ldc,
+                     const oz_opts_t* opts, void* workspace, size_t workspace_bytes,
+                     oz_result_t* results);
+
 /* Layout of the intermediate buffers inside the workspace after an oz_dgemm call, for
  * inspection by tests (all offsets in bytes from `workspace`):
  *   eA   int32[mp]              row exponents of op(A); -12288 marks an all-zero row

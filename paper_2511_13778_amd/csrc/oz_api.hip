@@ -450,6 +450,92 @@ oz_status_t oz_dgemm_static(oz_handle_t h, void* stream, char transa, char trans
                       size_t(OZ_STATIC_SCRATCH_BYTES), result);
 }
 
+namespace {
+
+// op in {N, T, C} of a complex operand: transposed? conjugated?
+bool parse_ztrans(char c, bool& t, bool& conj) {
+    conj = (c == 'C' || c == 'c');
+    if (conj) { t = true; return true; }
+    return parse_trans(c, t);
+}
+
+struct ZLayout {
+    size_t off_ar, off_ai, off_br, off_bi, off_pr, off_pi, off_ws, total;
+    size_t real_ws;
+};
+
+// planar copies of the stored A and B, the planar product, then the workspace of one real call
+// (the four real products run one after the other and share it)
+bool make_zlayout(oz_handle_t h, char ta_real, char tb_real, int64_t m, int64_t n, int64_t k, const oz_opts_t* opts,
+                  ZLayout& z) {
+    const size_t real_ws = oz_dgemm_workspace_bytes(h, ta_real, tb_real, m, n, k, opts);
+    if (real_ws == 0 && m > 0 && n > 0) return false;
+    size_t off = 0;
+    const size_t a = align_up(size_t(m) * k * 8), b = align_up(size_t(k) * n * 8), p = align_up(size_t(m) * n * 8);
+    z.off_ar = off; off += a;
+    z.off_ai = off; off += a;
+    z.off_br = off; off += b;
+    z.off_bi = off; off += b;
+    z.off_pr = off; off += p;
+    z.off_pi = off; off += p;
+    z.off_ws = off; off += align_up(real_ws);
+    z.real_ws = real_ws;
+    z.total = off;
+    return true;
+}
+
+}  // namespace
+
+size_t oz_zgemm_workspace_bytes(oz_handle_t h, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                const oz_opts_t* opts) {
+    bool ta, tb, ca, cb;
+    if (!h || !opts || !parse_ztrans(transa, ta, ca) || !parse_ztrans(transb, tb, cb)) return 0;
+    ZLayout z;
+    if (!make_zlayout(h, ta ? 'T' : 'N', tb ? 'T' : 'N', m, n, k, opts, z)) return 0;
+    return z.total;
+}
+
+oz_status_t oz_zgemm(oz_handle_t h, void* stream, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                     const double* alpha, const void* A, int64_t lda, const void* B, int64_t ldb,
+                     const double* beta, void* C, int64_t ldc, const oz_opts_t* opts, void* workspace,
+                     size_t workspace_bytes, oz_result_t* results) {
+    bool ta, tb, ca, cb;
+    if (!h || !opts || !alpha || !beta || !parse_ztrans(transa, ta, ca) || !parse_ztrans(transb, tb, cb)) return OZ_ERR_ARG;
+    if (!valid_opts(*opts)) return OZ_ERR_ARG;
+    if (m < 0 || n < 0 || k < 0 || !check_dims(ta, tb, m, n, k, lda, ldb, ldc)) return OZ_ERR_ARG;
+    if (m == 0 || n == 0) return OZ_OK;
+    if (!C || (k > 0 && (!A || !B))) return OZ_ERR_ARG;
+    const char tra = ta ? 'T' : 'N', trb = tb ? 'T' : 'N';
+    ZLayout z;
+    if (!make_zlayout(h, tra, trb, m, n, k, opts, z)) return OZ_ERR_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < z.total)
+        return OZ_ERR_WORKSPACE;
+    if (!on_handle_device(*h)) return OZ_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* w = static_cast<uint8_t*>(workspace);
+    double* Ar = reinterpret_cast<double*>(w + z.off_ar);
+    double* Ai = reinterpret_cast<double*>(w + z.off_ai);
+    double* Br = reinterpret_cast<double*>(w + z.off_br);
+    double* Bi = reinterpret_cast<double*>(w + z.off_bi);
+    double* Pr = reinterpret_cast<double*>(w + z.off_pr);
+    double* Pi = reinterpret_cast<double*>(w + z.off_pi);
+    // planar parts keep the stored shape (rows x cols of the stored matrix), leading dimension = rows
+    const int64_t a_rows = ta ? k : m, a_cols = ta ? m : k, b_rows = tb ? n : k, b_cols = tb ? k : n;
+    launch_zsplit(st, A, lda, a_rows, a_cols, Ar, Ai, ca);
+    launch_zsplit(st, B, ldb, b_rows, b_cols, Br, Bi, cb);
+    const int64_t pa = a_rows > 1 ? a_rows : 1, pb = b_rows > 1 ? b_rows : 1, pm = m;
+    struct Call { const double* a; const double* b; double alpha, beta; double* c; };
+    const Call calls[4] = {{Ar, Br, 1.0, 0.0, Pr}, {Ai, Bi, -1.0, 1.0, Pr}, {Ar, Bi, 1.0, 0.0, Pi}, {Ai, Br, 1.0, 1.0, Pi}};
+    for (int c = 0; c < 4; ++c) {
+        const oz_status_t s = dgemm_impl(h, stream, tra, trb, m, n, k, calls[c].alpha, calls[c].a, pa, calls[c].b, pb,
+                                         calls[c].beta, calls[c].c, pm, opts, w + z.off_ws, z.real_ws,
+                                         results ? results + c : nullptr);
+        if (s != OZ_OK) return s;
+    }
+    launch_zcombine(st, Pr, Pi, m, n, alpha[0], alpha[1], beta[0], beta[1], C, ldc);
+    return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
+}
+
 oz_status_t oz_dgemm_strided_batched(oz_handle_t h, void* stream, char transa, char transb, int64_t m,
                                      int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
                                      int64_t stride_a, const double* B, int64_t ldb, int64_t stride_b,

@@ -114,5 +114,11 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
                       int64_t k, double alpha, const double* A, int64_t lda, const double* B,
                       int64_t ldb, double beta, double* C, int64_t ldc);
 void launch_scale_c(hipStream_t st, int64_t m, int64_t n, double beta, double* C, int64_t ldc);
+// complex product by the 4M method: split an interleaved complex matrix into planar parts (conj negates
+// the imaginary part), and combine the planar product with alpha, beta and the interleaved C
+void launch_zsplit(hipStream_t st, const void* Z, int64_t ld, int64_t rows, int64_t cols, double* re, double* im,
+                   bool conj);
+void launch_zcombine(hipStream_t st, const double* Pr, const double* Pi, int64_t m, int64_t n, double ar, double ai,
+                     double br, double bi, void* C, int64_t ldc);
 
 }  // namespace oz

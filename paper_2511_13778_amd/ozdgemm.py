@@ -48,7 +48,7 @@ class oz_layout_t(C.Structure):
 
 
 EXPORTS = ("oz_create", "oz_destroy", "oz_default_opts", "oz_set_heuristic",
-           "oz_dgemm_workspace_bytes", "oz_dgemm", "oz_dgemm_static", "oz_dgemm_strided_batched", "oz_dgemm_layout", "oz_profile_enable",
+           "oz_dgemm_workspace_bytes", "oz_dgemm", "oz_dgemm_static", "oz_zgemm_workspace_bytes", "oz_zgemm", "oz_dgemm_strided_batched", "oz_dgemm_layout", "oz_profile_enable",
            "oz_profile_read", "oz_native_dgemm", "oz_status_string")
 
 _lib = None
@@ -89,6 +89,12 @@ def load_library() -> C.CDLL:
     lib.oz_dgemm.restype = C.c_int
     lib.oz_dgemm_static.argtypes = [H, C.c_void_p] + dims + gemm_args + [C.POINTER(oz_opts_t), C.c_void_p]
     lib.oz_dgemm_static.restype = C.c_int
+    lib.oz_zgemm_workspace_bytes.argtypes = [H] + dims + [C.POINTER(oz_opts_t)]
+    lib.oz_zgemm_workspace_bytes.restype = C.c_size_t
+    lib.oz_zgemm.argtypes = [H, C.c_void_p] + dims + [C.POINTER(C.c_double), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                                       C.POINTER(C.c_double), C.c_void_p, C.c_int64, C.POINTER(oz_opts_t),
+                                                       C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.oz_zgemm.restype = C.c_int
     lib.oz_dgemm_strided_batched.argtypes = [H, C.c_void_p] + dims + [
         C.c_double, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_double, C.c_void_p,
         C.c_int64, C.c_int64, C.c_int64, C.POINTER(oz_opts_t), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -191,6 +197,16 @@ class Handle:
         _check(self.lib.oz_dgemm_static(self._h, stream_ptr, transa.encode(), transb.encode(), m, n, k, alpha,
                                         A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc, C.byref(opts), result_ptr),
                "oz_dgemm_static")
+
+    def zgemm_workspace_bytes(self, transa, transb, m, n, k, opts: oz_opts_t) -> int:
+        return int(self.lib.oz_zgemm_workspace_bytes(self._h, transa.encode(), transb.encode(), m, n, k, C.byref(opts)))
+
+    def zgemm(self, stream_ptr, transa, transb, m, n, k, alpha: complex, A_ptr, lda, B_ptr, ldb, beta: complex, C_ptr,
+              ldc, opts: oz_opts_t, ws_ptr, ws_bytes, results_ptr=None):
+        al = (C.c_double * 2)(complex(alpha).real, complex(alpha).imag)
+        be = (C.c_double * 2)(complex(beta).real, complex(beta).imag)
+        _check(self.lib.oz_zgemm(self._h, stream_ptr, transa.encode(), transb.encode(), m, n, k, al, A_ptr, lda, B_ptr,
+                                 ldb, be, C_ptr, ldc, C.byref(opts), ws_ptr, ws_bytes, results_ptr), "oz_zgemm")
 
     def dgemm_strided_batched(self, stream_ptr, transa, transb, m, n, k, alpha, A_ptr, lda, stride_a, B_ptr, ldb,
                               stride_b, beta, C_ptr, ldc, stride_c, batch_count, opts: oz_opts_t, ws_ptr, ws_bytes,

@@ -125,6 +125,15 @@ def test_transposes(lib, ta, tb):
     check_against_oracle(g, h, A, B, mode="dynamic", max_bits=200, transa=ta, transb=tb, pad=5)
 
 
+def test_alpha_beta_round_separately(lib):
+    # alpha and beta that are not powers of two: alpha*AB and beta*C are rounded on their own and then
+    # added (no fused multiply-add), which is what the oracle does; a fused epilogue differs in the last bit
+    g, h = lib
+    A, B, Cin = wl.lognormal_spread(257, 300, 130, 0.5, seed=33, with_c=True)
+    check_against_oracle(g, h, A, B, 1.1, 0.3, Cin, mode="forced", max_bits=55, pad=1)
+    check_against_oracle(g, h, A, B, -0.7, 1.9, Cin, mode="dynamic", max_bits=200, transa="T")
+
+
 def test_int32_k_blocking(lib):
     # S = 7 takes 18688 k per int32 accumulator: 19000 needs two k-blocks
     g, h = lib
@@ -598,6 +607,60 @@ def test_concurrent_slice_gemms_share_the_chip(lib):
     want = oz.recompose(P, eA[I], eB[J])
     got = outs[1][0].index_select(0, torch.as_tensor(J, device="cuda")).index_select(1, torch.as_tensor(I, device="cuda"))
     np.testing.assert_array_equal(got.cpu().numpy().T, want)
+
+
+@pytest.mark.parametrize("ta,tb,beta", [("N", "N", 0.0), ("T", "N", complex(0.5, 2.0)), ("N", "C", complex(-1.0, 0.25)),
+                                        ("C", "T", 0.0)])
+def test_zgemm_4m(lib, ta, tb, beta):
+    # complex product by the 4M method: four real products through the emulated DGEMM (each with its own
+    # record), combined in a fixed order: bit-identical to the oracle's, and inside the componentwise bound
+    # of the exact complex product on sampled entries
+    g, h = lib
+    rng = np.random.default_rng(hash((ta, tb)) % 1000)
+    m, n, k = 150, 270, 333
+    cplx = lambda shape: (rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * np.exp2(rng.integers(-4, 5, shape))
+    A, B, Cin = cplx((m, k)), cplx((k, n)), cplx((m, n))
+    alpha = complex(1.25, -0.5)
+    op = {"N": lambda X: X, "T": lambda X: X.T, "C": lambda X: X.conj().T}
+    # stored operands: op(stored) = logical, so stored = op^-1(logical); T and C are their own inverses
+    sA, sB = np.ascontiguousarray(op[ta](A)), np.ascontiguousarray(op[tb](B))
+    dA = torch.from_numpy(np.ascontiguousarray(sA.T)).cuda()           # column-major storage of the stored matrix
+    dB = torch.from_numpy(np.ascontiguousarray(sB.T)).cuda()
+    dC = torch.from_numpy(np.ascontiguousarray(Cin.T)).cuda() if beta != 0.0 else \
+        torch.full((n, m), complex(float("nan"), float("nan")), dtype=torch.complex128, device="cuda")
+    opts = g.make_opts(mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200, heuristic=0, tile_slices=0)
+    ws_bytes = h.zgemm_workspace_bytes(ta, tb, m, n, k, opts)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    recs = torch.zeros((4, g.RESULT_INT32_WORDS), dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    h.zgemm(st, ta, tb, m, n, k, alpha, dA.data_ptr(), sA.shape[0], dB.data_ptr(), sB.shape[0], beta, dC.data_ptr(), m,
+            opts, ws.data_ptr(), ws_bytes, recs.data_ptr())
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy().T
+    want, verdicts = oz.emulated_zgemm(A, B, alpha, beta, Cin, mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200)
+    for r, v in zip(recs.cpu().tolist(), verdicts):
+        r = g.result_from_words(r)
+        assert (r.fallback, r.reason, r.slices_used, r.esc, r.required_bits) == \
+               (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits)
+    np.testing.assert_array_equal(got.real, want.real)
+    np.testing.assert_array_equal(got.imag, want.imag)
+    # exact complex reference on sampled entries (rational arithmetic)
+    from fractions import Fraction as F
+    absA, absB = np.abs(A.real) + np.abs(A.imag), np.abs(B.real) + np.abs(B.imag)
+    b = complex(beta)
+    for i, j in [(0, 0), (m - 1, n - 1), (77, 131), (3, 200), (149, 1)]:
+        pr = sum(F(float(A[i, l].real)) * F(float(B[l, j].real)) - F(float(A[i, l].imag)) * F(float(B[l, j].imag)) for l in range(k))
+        pi = sum(F(float(A[i, l].real)) * F(float(B[l, j].imag)) + F(float(A[i, l].imag)) * F(float(B[l, j].real)) for l in range(k))
+        re = F(alpha.real) * pr - F(alpha.imag) * pi
+        im = F(alpha.real) * pi + F(alpha.imag) * pr
+        den = (abs(alpha.real) + abs(alpha.imag)) * float(absA[i] @ absB[:, j])
+        if beta != 0.0:
+            re += F(b.real) * F(float(Cin[i, j].real)) - F(b.imag) * F(float(Cin[i, j].imag))
+            im += F(b.real) * F(float(Cin[i, j].imag)) + F(b.imag) * F(float(Cin[i, j].real))
+            den += (abs(b.real) + abs(b.imag)) * (abs(Cin[i, j].real) + abs(Cin[i, j].imag))
+        tol = (k + 4) * 2.0 ** -53 * den
+        assert abs(F(float(got[i, j].real)) - re) <= tol and abs(F(float(got[i, j].imag)) - im) <= tol
 
 
 def test_strided_batched(lib):
