@@ -64,11 +64,10 @@ SHAPES = [(16384, 16384, 512), (1024, 1024, 65536), (32768, 256, 8192), (4096, 4
 
 
 def shapes(torch, g, h, reps):
-    from oracle import ozaki as oz   # host-side cost model only (the same integers the library uses)
     from paper_2511_13778_amd import workloads as wl
     st = torch.cuda.current_stream().cuda_stream
     lines = ["# rectangular problems, row i of A scaled by 2^(i mod 40), alpha = 1, beta = 0; %d timed calls per entry" % reps,
-             "# heuristic: what DYNAMIC mode with the cost model on would do with 7 slices (the fewest a call can get)",
+             "# heuristic: what the library decides for this input with its default options (DYNAMIC, cost model on)",
              "m      n      k      | emulated forced 55: ms TFLOP/s (gemm recompose slicing ms) | own FP64 ms | vendor FP64 ms | x vendor | heuristic"]
     for m, n, k in SHAPES:
         print("shape %d %d %d" % (m, n, k), flush=True)
@@ -86,10 +85,15 @@ def shapes(torch, g, h, reps):
         t_own = timed(torch, lambda: h.native_dgemm(st, "N", "N", m, n, k, 1.0, dA.data_ptr(), m, dB.data_ptr(), k, 0.0,
                                                     dC.data_ptr(), m), reps)
         t_ven = timed(torch, lambda: torch.matmul(dB, dA), reps)
-        slower = oz.HeuristicModel().emulation_slower(7, m, n, k)
+        gd = g.Gemm(h, m, n, k, g.default_opts())
+        gd.run(dA, m, dB, k, dC, m, 1.0, 0.0)
+        torch.cuda.synchronize()
+        rd = gd.result()
+        slower = bool(rd.fallback)
+        del gd
         lines.append("%-6d %-6d %-6d | %8.3f %6.1f (%.3f %.3f %.3f) | %8.3f | %8.3f | %5.2f | %s"
                      % (m, n, k, ms, 2.0 * m * n * k / ms * 1e-9, sm["slice_gemm_i8"], sm["recompose"], sm["slicing"],
-                        t_own, t_ven, t_ven / ms, "native" if slower else "emulate"))
+                        t_own, t_ven, t_ven / ms, ("native (reason %d)" % rd.reason) if slower else "emulate, S = %d" % rd.slices_used))
         del dA, dB, dC, gm
         torch.cuda.empty_cache()
     with open(os.path.join(OUT, "throughput_shapes.txt"), "w") as f:

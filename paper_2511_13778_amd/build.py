@@ -15,8 +15,8 @@ PROBE_SOURCES = ["oz_probe.hip"]
 SOURCES = ["oz_api.hip", "oz_scan.hip", "oz_esc.hip", "oz_slice.hip", "oz_gemm_i8.hip",
            "oz_recompose.hip", "oz_dgemm_f64.hip", "oz_complex.hip"]
 # packed FP32 instructions are switched off for all device code (known-bad on the test machines)
-# -ffp-contract=off: the FP64 epilogues round every product and sum separately, as their specification and
-# the CPU oracle do; hipcc's default would fuse a*b + c into one rounding.
+# -ffp-contract=off: the FP64 epilogues round every product and sum separately, as the header specifies;
+# hipcc's default would fuse a*b + c into one rounding.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
          "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -77,3 +77,34 @@ def test_no_cpu_fallback_in_binding():
     for name in ("ozdgemm.py", "ozprobe.py", "qr.py", "build.py", "workloads.py", "__init__.py"):
         src = open(os.path.join(ROOT, "paper_2511_13778_amd", name)).read()
         assert "oracle" not in src.replace("CPU oracle's tests", ""), name
+
+
+def test_only_the_allowed_places_use_the_oracle():
+    # the oracle is test infrastructure: besides tests/, only smoke() and bench.py's cpu_baseline leg import it
+    import ast
+    def oracle_imports(path):
+        tree = ast.parse(open(path).read())
+        hits = []
+        for node in ast.walk(tree):
+            if isinstance(node, ast.ImportFrom) and (node.module or "").split(".")[0] == "oracle":
+                hits.append(node.lineno)
+            if isinstance(node, ast.Import) and any(a.name.split(".")[0] == "oracle" for a in node.names):
+                hits.append(node.lineno)
+        return hits
+    for folder in ("experiments", "paper_2511_13778_amd"):
+        for name in sorted(os.listdir(os.path.join(ROOT, folder))):
+            if name.endswith(".py"):
+                assert oracle_imports(os.path.join(ROOT, folder, name)) == [], (folder, name)
+    # bench.py: only inside cpu_baseline; __graft_entry__.py: only inside smoke
+    for fname, func in (("bench.py", "cpu_baseline"), ("__graft_entry__.py", "smoke")):
+        tree = ast.parse(open(os.path.join(ROOT, fname)).read())
+        allowed = set()
+        for node in tree.body:
+            if isinstance(node, ast.FunctionDef) and node.name == func:
+                allowed = {n.lineno for n in ast.walk(node) if isinstance(n, (ast.Import, ast.ImportFrom))}
+        assert set(oracle_imports(os.path.join(ROOT, fname))) <= allowed, fname
+    # and the oracle never reaches for the product
+    for name in os.listdir(os.path.join(ROOT, "oracle")):
+        if name.endswith(".py"):
+            src = open(os.path.join(ROOT, "oracle", name)).read()
+            assert "paper_2511_13778_amd" not in src and "ctypes" not in src, name
