@@ -1,4 +1,4 @@
-"""GPU parity at BASELINE's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
 
 The oracle cannot run 8192^3 in full, so it is evaluated on sampled rows of op(A) and columns of
 op(B) (first, last and random ones, so that many tiles and both tile edges are hit): row/column
