@@ -749,6 +749,26 @@ def test_call_can_be_captured_in_a_graph(lib):
         torch.cuda.synchronize()
         assert torch.equal(dC, ref)
     assert gm.result().fallback == 0
+    # the decision is taken on the device, so the same captured graph serves a call that falls back: plant a
+    # NaN in A, replay, compare with the eager call on the same operands, then heal A and replay once more
+    keep = dA[5, 7].item()
+    dA[5, 7] = float("nan")
+    dC.fill_(0.0)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    r = gm.result()
+    assert (r.fallback, r.reason) == (1, oz.REASON_INFNAN)
+    replayed = dC.clone()
+    dC.fill_(0.0)
+    gm.run(dA, n, dB, n, dC, n)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.isnan(dC), torch.isnan(replayed)) and torch.isnan(dC).any()
+    assert torch.equal(torch.nan_to_num(dC), torch.nan_to_num(replayed))
+    dA[5, 7] = keep
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(dC, ref) and gm.result().fallback == 0
 
 
 def test_argument_errors(lib):
