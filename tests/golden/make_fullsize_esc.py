@@ -31,6 +31,9 @@ CASES = {
     "rowscaled_16384x16384x512_seed6": lambda: wl.row_scaled(16384, 512, 16384, seed=6)[:2],
     "widespan_2048_seed7": lambda: wl.wide_span(2048, 2048, 2048, seed=7),
     "rank1_2048_seed9": lambda: wl.rank1_cancel(2048, 2048, 2048, seed=9),
+    # m, then n, at the library's limit of 2^22
+    "lognormal_4194304x300x24_seed26": lambda: wl.lognormal_spread(1 << 22, 24, 300, 1.0, seed=26),
+    "lognormal_300x4194304x24_seed27": lambda: wl.lognormal_spread(300, 24, 1 << 22, 1.0, seed=27),
 }
 
 # workloads whose per-block ESC table (256 x 256 blocks of C) is stored, one file each:

@@ -336,6 +336,24 @@ def test_longest_k(lib):
     assert res.slices_used == 7
 
 
+@pytest.mark.parametrize("tall", [True, False])
+def test_largest_m_and_n(lib, tall):
+    # m, then n, at the library's limit (2^22): a strip of 16384 x 2 tiles of C, 64 rounds of the slice
+    # GEMM's workgroups, element offsets past 2^31 and byte offsets past 2^32 inside the leading-word and
+    # digit planes, and 65536-wide launches of the scan, slicing and recomposition kernels
+    g, h = lib
+    if tall:
+        A, B = wl.lognormal_spread(1 << 22, 24, 300, 1.0, seed=26)
+        name = "lognormal_4194304x300x24_seed26"
+    else:
+        A, B = wl.lognormal_spread(300, 24, 1 << 22, 1.0, seed=27)
+        name = "lognormal_300x4194304x24_seed27"
+    res, ratio = sampled_parity(g, h, A, B, 1.0, 0.0, None, "dynamic", 200, name, nsample=40)
+    assert res.fallback == 0 and res.slices_used == oz.slices_dynamic(53, res.esc) == 10
+    _inputs.clear()
+    torch.cuda.empty_cache()
+
+
 def test_reproducible_across_calls(lib):
     # integer accumulation is order-free and the FP64 order is fixed: C is bit-identical run to run
     g, h = lib
