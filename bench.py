@@ -202,12 +202,15 @@ def main():
     if stage_ms["slicing"] > 0 and S:
         hbm["slicing"] = {"bytes": (8 + S) * (mk + kn), "GBps": (8 + S) * (mk + kn) / (stage_ms["slicing"] * 1e-3) * 1e-9}
     if stage_ms["recompose"] > 0 and S:
-        byts = (4 * S + 8 + (8 if beta != 0 else 0)) * mn
+        # per k-block an int32 leading word and S-1 one-byte digits per element, then C (read only if beta != 0)
+        nkb = int(h.layout("N", "N", m, n, k, opts).nkb)
+        byts = ((4 + (S - 1)) * nkb + 8 + (8 if beta != 0 else 0)) * mn
         hbm["recompose"] = {"bytes": byts, "GBps": byts / (stage_ms["recompose"] * 1e-3) * 1e-9}
     for v in hbm.values():
         v["frac_of_hbm_peak"] = v["GBps"] / HBM_PEAK_GBS
         if ceilings:
             v["frac_of_copy_kernel"] = v["GBps"] / ceilings["copy_kernel_GBps"]
+            v["frac_of_read_kernel"] = v["GBps"] / ceilings["read_kernel_GBps"]
     guard_ms = stage_ms["scan"] + stage_ms["esc"] + stage_ms["verdict"]
 
     native = {}
