@@ -443,6 +443,67 @@ def test_randomized_configurations(lib, seed):
                          pad=int(rng.integers(0, 4)), bound=(mode == "dynamic"))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_randomized_configurations_multi_tile(lib, seed):
+    # the same draw over shapes that span several 256 x 256 blocks of C, a k split or several rounds, wider
+    # exponent spreads, operands scaled towards the ends of the FP64 range, other target precisions
+    g, h = lib
+    rng = np.random.default_rng(5000 + seed)
+    m, n, k = int(rng.integers(1, 900)), int(rng.integers(1, 900)), int(rng.integers(1, 1500))
+    phi = float(rng.choice([0.0, 0.3, 1.0, 2.0, 4.0]))
+    A, B, Cin = wl.lognormal_spread(m, k, n, phi, seed=7000 + seed, with_c=True)
+    if rng.random() < 0.3:
+        A[rng.random(A.shape) < 0.05] = 0.0
+        A[int(rng.integers(m)), :] = 0.0
+        B[:, int(rng.integers(n))] = 0.0
+    if rng.random() < 0.25:
+        A *= 2.0 ** float(rng.integers(-1000, 900))
+    mode = str(rng.choice(["dynamic", "forced", "fixed_guarded", "unguarded"]))
+    alpha = float(rng.choice([1.0, -1.0, 0.75, 3.0, 1.1]))
+    beta = float(rng.choice([0.0, 1.0, -0.5, 0.3]))
+    ta, tb = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+    max_bits = 200 if mode == "dynamic" else int(rng.choice([23, 39, 55, 63, 87]))
+    tbits = int(rng.choice([53, 53, 40, 64])) if mode == "dynamic" else 53
+    check_against_oracle(g, h, A, B, alpha, beta, Cin if beta != 0.0 else None, mode=mode, max_bits=max_bits,
+                         target_bits=tbits, esc_block=int(rng.choice([0, 16, 32, 128])), transa=ta, transb=tb,
+                         pad=int(rng.integers(0, 4)), bound=(mode == "dynamic" and tbits >= 53))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_randomized_per_tile_slice_counts(lib, seed):
+    # per-block slice counts on drawn shapes and inputs (a band of difficult rows, i.i.d. spreads, zeros in both
+    # operands), with and without the cost model: record, per-block counts and C bit for bit
+    g, h = lib
+    rng = np.random.default_rng(9000 + seed)
+    m, n, k = int(rng.integers(1, 1100)), int(rng.integers(1, 1100)), int(rng.integers(1, 900))
+    kind = int(rng.integers(3))
+    if kind == 0 and m > 40:
+        r0 = int(rng.integers(0, m - 20))
+        A, B = wl.wide_rows(m, k, n, seed=seed, row_lo=r0, row_hi=r0 + int(rng.integers(1, 20)),
+                            spread=int(rng.integers(8, 60)))
+    else:
+        A, B = wl.lognormal_spread(m, k, n, float(rng.choice([0.3, 1.0, 3.0])), seed=seed)
+        if kind == 2:
+            A[rng.random(A.shape) < 0.1] = 0.0
+            B[rng.random(B.shape) < 0.1] = 0.0
+    Cin = rng.standard_normal((m, n))
+    alpha, beta = float(rng.choice([1.0, 1.5, -0.7])), float(rng.choice([0.0, 0.5]))
+    ta, tb = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+    tbits = int(rng.choice([53, 53, 45, 61]))
+    hz = int(rng.integers(2))
+    got, gm, res = run_gpu(g, h, A, B, alpha, beta, Cin if beta else None, ta, tb, pad=int(rng.integers(0, 3)),
+                           mode=g.OZ_DYNAMIC, target_bits=tbits, max_bits=200, heuristic=hz, tile_slices=1)
+    tr = oz.emulated_dgemm(A, B, alpha, beta, Cin if beta else None, mode=oz.MODE_DYNAMIC, target_bits=tbits,
+                           max_bits=200, per_tile=True, heuristic=oz.HeuristicModel() if hz else None)
+    v = tr.verdict
+    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan, res.slices_min,
+            res.pair_tiles) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan, v.slices_min,
+                                v.pair_tiles)
+    if not v.fallback:
+        np.testing.assert_array_equal(gm.tile_slice_counts(), tr.S_tile)
+        np.testing.assert_array_equal(got, tr.C)
+
+
 @pytest.mark.parametrize("ta,tb,seed", [("N", "N", 0), ("T", "N", 1), ("N", "T", 2), ("T", "T", 3)])
 def test_per_tile_slice_counts(lib, ta, tb, seed):
     # OZ_DYNAMIC with tile_slices: a band of difficult rows makes the blocks of C it crosses need more
