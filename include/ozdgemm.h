@@ -109,12 +109,15 @@ typedef struct {
 
 /* Section "GPU-Resident Integration": the whole decision process lives on the device, so the
  * host-side state is small.  Creates a handle bound to HIP device `device` (must be gfx950): the
- * device's compute-unit count, the cost-model constants of the run-time heuristic and the event
- * pool of the stage timer.  Allocates host memory only; *handle is NULL on failure.
- * Errors: OZ_ERR_ARG (handle NULL), OZ_ERR_DEVICE (no such device / not gfx950). */
+ * device's compute-unit count, the cost-model constants of the run-time heuristic, the event
+ * pool of the stage timer, the side streams (default priority) and events of the batched call, and
+ * the device address of the static workspace of oz_dgemm_static on that device.  Allocates host
+ * memory, streams and events, no device memory; *handle is NULL on failure.
+ * Errors: OZ_ERR_ARG (handle NULL), OZ_ERR_DEVICE (no such device / not gfx950), OZ_ERR_HIP (the
+ * static workspace's address could not be resolved). */
 oz_status_t oz_create(oz_handle_t* handle, int device);
 
-/* Releases what oz_create made (host memory, events).  Work already enqueued with the handle is
+/* Releases what oz_create made (host memory, streams, events).  Work already enqueued with the handle is
  * not waited for: it only references caller-owned device memory.  OZ_ERR_ARG on NULL. */
 oz_status_t oz_destroy(oz_handle_t handle);
 
