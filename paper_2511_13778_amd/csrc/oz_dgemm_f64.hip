@@ -42,15 +42,45 @@ __device__ __forceinline__ void dg_load(double (&v)[T / 16], const double* __res
     }
 }
 // interior tiles (no bounds to check): `u` is the wave-uniform address of the K step of this tile,
-// `vo` this thread's byte offset inside it (fixed for the whole kernel), the eight elements of a
-// thread are qstep elements apart.  Uniform base + 32-bit lane offset keeps the addresses in
-// scalar registers.
-template <int T>
-__device__ __forceinline__ void dg_load_interior(double (&v)[T / 16], const double* __restrict__ u, uint32_t vo,
-                                                 int64_t qstep) {
+// `vo` this thread's byte offset inside it (fixed for the whole kernel), the elements of a thread are
+// qstep_bytes apart.  The loads go through a buffer descriptor built on `u` (48-bit base in scalar
+// registers, element distance as the instruction's scalar offset, `vo` as its 32-bit lane offset), so a
+// K step has no vector address arithmetic at all.  Written as plain loads from `u + q*qstep + vo` the
+// compiler keeps a 64-bit per-lane address for every element and rebuilds all of them with 64-bit
+// vector adds in every K step: some forty vector instructions that compete with the MFMAs for the
+// issue slot (measured at 8192^3: 15.36 ms with those, 14.70 ms with the descriptor form).
+// The descriptor covers 4 GiB from `u` (raw buffer, no swizzle); the launcher sends operands whose
+// offsets could exceed that to the bounds-checked path.
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+// PER_Q: every element of a thread has a lane offset of its own (ragged tiles of a k-contiguous
+// operand, whose rows are clamped one by one); otherwise one lane offset and q * qstep_bytes.
+template <int T, bool PER_Q>
+__device__ __forceinline__ void dg_load_fast(double (&v)[T / 16], const double* u, const uint32_t (&vo)[PER_Q ? T / 16 : 1],
+                                             uint32_t qstep_bytes) {
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(u), 0, -1, 0x00020000);
 #pragma unroll
-    for (int q = 0; q < T / 16; ++q)
-        v[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(u + q * qstep) + vo);
+    for (int q = 0; q < T / 16; ++q) {
+        const v2u x = __builtin_amdgcn_raw_buffer_load_b64(r, int(vo[PER_Q ? q : 0]),
+                                                           PER_Q ? 0 : int(uint32_t(q) * qstep_bytes), 0);
+        v[q] = __builtin_bit_cast(double, x);
+    }
+}
+// lane offsets (bytes) of a thread's elements inside a K step of a tile that has `vr` (1..T) valid rows:
+// rows past the last valid one are read from the last valid one instead (their products land in rows
+// or columns of C that are never stored), so every address stays inside the operand
+template <bool ROWS_CONTIG, int T, bool PER_Q>
+__device__ __forceinline__ void dg_lane_offsets(uint32_t (&vo)[PER_Q ? T / 16 : 1], int64_t stride_r, int64_t stride_l,
+                                                int vr) {
+    if (ROWS_CONTIG) {
+        const int rr = min(int(threadIdx.x & (T - 1)), vr - 1);
+        vo[0] = uint32_t(rr * stride_r + (threadIdx.x / T) * stride_l) * 8u;
+    } else {
+#pragma unroll
+        for (int q = 0; q < (PER_Q ? T / 16 : 1); ++q) {
+            const int rr = min(int(threadIdx.x >> 4) + 16 * q, vr - 1);
+            vo[q] = uint32_t(rr * stride_r + (threadIdx.x & 15) * stride_l) * 8u;
+        }
+    }
 }
 
 template <bool ROWS_CONTIG, int T>
@@ -64,11 +94,19 @@ __device__ __forceinline__ void dg_store(const double (&v)[T / 16], double* lds)
     }
 }
 
-template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, bool EDGE, int T>
+// MODE 0: m, n multiples of the tile and k of the K step.  MODE 1: any m, n, k: edge tiles clamp their
+// rows in the (loop-invariant) lane offsets and k % 16 is taken as a short first K step, loaded by the
+// bounds-checked loader once per tile; the K loop itself is the same as in MODE 0.  MODE 2: the
+// bounds-checked loader with 64-bit indexing everywhere (operands whose leading dimension does not
+// fit the 32-bit offsets of the fast loads).
+template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, int MODE, int T>
 __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     const Record* rec, int64_t m, int64_t n, int64_t k, double alpha, const double* __restrict__ A,
     int64_t a_sr, int64_t a_sl, const double* __restrict__ B, int64_t b_sr, int64_t b_sl, double beta,
     double* __restrict__ C, int64_t ldc, int ntm, int ntn) {
+    constexpr bool EDGE = MODE == 2;                       // bounds-checked loads in the K loop
+    constexpr bool RAGGED = MODE != 0;                     // bounds-checked stores of C
+    constexpr bool A_PER_Q = MODE == 1 && !A_ROWS_CONTIG, B_PER_Q = MODE == 1 && !B_ROWS_CONTIG;
     constexpr int kDLd = T + kDPad;      // LDS row length
     constexpr int WT = T / 2;            // wave tile
     constexpr int MT = WT / 16;          // MFMA tiles per wave and direction
@@ -104,20 +142,21 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         for (int b = 0; b < MT; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
 
     double va[EPT], vb[EPT];
-    // EDGE == false: m, n multiples of the tile and k a multiple of the K step
     const double* ua = A + i0 * a_sr;   // wave-uniform: start of this tile's rows at k = 0
     const double* ub = B + j0 * b_sr;
-    const uint32_t voa = uint32_t(A_ROWS_CONTIG ? (threadIdx.x & (T - 1)) * a_sr + (threadIdx.x / T) * a_sl
-                                                : (threadIdx.x >> 4) * a_sr + (threadIdx.x & 15) * a_sl) * 8u;
-    const uint32_t vob = uint32_t(B_ROWS_CONTIG ? (threadIdx.x & (T - 1)) * b_sr + (threadIdx.x / T) * b_sl
-                                                : (threadIdx.x >> 4) * b_sr + (threadIdx.x & 15) * b_sl) * 8u;
-    const int64_t qa = A_ROWS_CONTIG ? (256 / T) * a_sl : 16 * a_sr, qb = B_ROWS_CONTIG ? (256 / T) * b_sl : 16 * b_sr;
-    if (EDGE) {
-        dg_load<A_ROWS_CONTIG, T>(va, A, a_sr, a_sl, i0, m, 0, k);
-        dg_load<B_ROWS_CONTIG, T>(vb, B, b_sr, b_sl, j0, n, 0, k);
+    uint32_t voa[A_PER_Q ? EPT : 1], vob[B_PER_Q ? EPT : 1];
+    dg_lane_offsets<A_ROWS_CONTIG, T, A_PER_Q>(voa, a_sr, a_sl, MODE == 1 ? int(min(int64_t(T), m - i0)) : T);
+    dg_lane_offsets<B_ROWS_CONTIG, T, B_PER_Q>(vob, b_sr, b_sl, MODE == 1 ? int(min(int64_t(T), n - j0)) : T);
+    const uint32_t qa = uint32_t(A_ROWS_CONTIG ? (256 / T) * a_sl : 16 * a_sr) * 8u;   // bytes between a thread's elements
+    const uint32_t qb = uint32_t(B_ROWS_CONTIG ? (256 / T) * b_sl : 16 * b_sr) * 8u;
+    // length of the first K step: k % 16 (a full step when that is zero); only MODE 1 has a short one
+    const int kfirst = (MODE == 1 && (k & (kDK - 1))) ? int(k & (kDK - 1)) : kDK;
+    if (EDGE || kfirst != kDK) {
+        dg_load<A_ROWS_CONTIG, T>(va, A, a_sr, a_sl, i0, m, 0, EDGE ? k : kfirst);
+        dg_load<B_ROWS_CONTIG, T>(vb, B, b_sr, b_sl, j0, n, 0, EDGE ? k : kfirst);
     } else {
-        dg_load_interior<T>(va, ua, voa, qa);
-        dg_load_interior<T>(vb, ub, vob, qb);
+        dg_load_fast<T, A_PER_Q>(va, ua, voa, qa);
+        dg_load_fast<T, B_PER_Q>(vb, ub, vob, qb);
     }
     dg_store<A_ROWS_CONTIG, T>(va, At[0]);
     dg_store<B_ROWS_CONTIG, T>(vb, Bt[0]);
@@ -149,18 +188,22 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     double xa[MT], xb[MT], ya[MT], yb[MT];
     int buf = 0;
     OZ_DG_READ(xa, xb, 0, 0);
-    for (int64_t l0 = 0; l0 < k; l0 += kDK) {
-        const bool have_next = l0 + kDK < k;
+    // K steps: [0, kfirst), then full steps of 16.  l0 is where the current step ends = the next one starts
+    int64_t adv = kfirst;               // distance from the current step's start to the next one's
+    for (int64_t l0 = kfirst;; l0 += kDK) {
+        const bool have_next = l0 < k;
         if (EDGE) {
             if (have_next) {
-                dg_load<A_ROWS_CONTIG, T>(va, A, a_sr, a_sl, i0, m, l0 + kDK, k);
-                dg_load<B_ROWS_CONTIG, T>(vb, B, b_sr, b_sl, j0, n, l0 + kDK, k);
+                dg_load<A_ROWS_CONTIG, T>(va, A, a_sr, a_sl, i0, m, l0, k);
+                dg_load<B_ROWS_CONTIG, T>(vb, B, b_sr, b_sl, j0, n, l0, k);
             }
         } else {
-            ua += have_next ? kDK * a_sl : 0;
-            ub += have_next ? kDK * b_sl : 0;
-            dg_load_interior<T>(va, ua, voa, qa);
-            dg_load_interior<T>(vb, ub, vob, qb);
+            // the last K step loads its own tile again (valid addresses, stored where nobody reads it)
+            ua += have_next ? adv * a_sl : 0;
+            ub += have_next ? adv * b_sl : 0;
+            adv = kDK;
+            dg_load_fast<T, A_PER_Q>(va, ua, voa, qa);
+            dg_load_fast<T, B_PER_Q>(vb, ub, vob, qb);
         }
         OZ_DG_READ(ya, yb, buf, 1);
         OZ_DG_MFMA(xa, xb);
@@ -197,6 +240,7 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
         }
+        if (!have_next) break;
     }
 #undef OZ_DG_READ
 #undef OZ_DG_MFMA
@@ -210,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
             for (int r = 0; r < 4; ++r) {
                 const int64_t j = j0 + wj * WT + fj * 16 + 4 * r + (lane >> 4);
                 const int64_t i = i0 + wi * WT + fi * 16 + (lane & 15);
-                if (!EDGE || (i < m && j < n)) {
+                if (!RAGGED || (i < m && j < n)) {
                     double out = __dmul_rn(alpha, acc[fj][fi][r]);
                     if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
                     C[j * ldc + i] = out;
@@ -234,18 +278,22 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
     const int T = small ? 64 : 128;
     const int ntm = int((m + T - 1) / T), ntn = int((n + T - 1) / T);
     const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
-    // the interior path keeps each lane's offset inside a tile in 32 bits (at most 15 leading
-    // dimensions plus a row of the tile, in bytes); operands cut out of a very large parent matrix
-    // take the bounds-checked path, which indexes in 64 bits
+    // the interior path keeps every offset inside a K step of a tile in 32 bits (a lane's own: at most
+    // 15 leading dimensions plus a row of the tile; its elements: up to 7 x 16 leading dimensions
+    // further on; in bytes); operands cut out of a very large parent matrix take the bounds-checked
+    // path, which indexes in 64 bits
     const int64_t ld_max = lda > ldb ? lda : ldb;
-    const bool wide_ld = (15 * ld_max + 256) * 8 >= (int64_t(1) << 32);
-    const bool edge = (m % T) || (n % T) || (k % kDK) || wide_ld;
+    const bool wide_ld = (128 * ld_max + 256) * 8 >= (int64_t(1) << 32);
+    // k < 16: the fast loads always fetch a full K step, which such a matrix does not have
+    const int mode = (wide_ld || k < kDK) ? 2 : (((m % T) || (n % T) || (k % kDK)) ? 1 : 0);
+#define OZ_DG_M(AC, BC, MODE, TT)                                                                              \
+    hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, MODE, TT>), grid, block, 0, st, rec, m, n, k, alpha, A, a_sr, \
+                       a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn)
 #define OZ_DG_T(AC, BC, TT)                                                                                    \
     {                                                                                                          \
-        if (edge) hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, true, TT>), grid, block, 0, st, rec, m, n, k,   \
-                                     alpha, A, a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);             \
-        else hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, false, TT>), grid, block, 0, st, rec, m, n, k,       \
-                                alpha, A, a_sr, a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn);                  \
+        if (mode == 2) OZ_DG_M(AC, BC, 2, TT);                                                                 \
+        else if (mode == 1) OZ_DG_M(AC, BC, 1, TT);                                                            \
+        else OZ_DG_M(AC, BC, 0, TT);                                                                           \
     }
 #define OZ_DG(AC, BC)                                                                                          \
     {                                                                                                          \
@@ -256,6 +304,7 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
     else if (!ac && bc) OZ_DG(false, true)
     else OZ_DG(false, false)
 #undef OZ_DG_T
+#undef OZ_DG_M
 #undef OZ_DG
 }
 

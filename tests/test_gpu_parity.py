@@ -405,7 +405,8 @@ def test_heuristic_after_the_esc(lib):
 
 
 # 64-tiles: ragged and interior; 128-tiles (at least 256 of them): ragged and interior
-@pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512), (2100, 2050, 50), (2048, 2048, 64)])
+@pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512), (2100, 2050, 50), (2048, 2048, 64), (33, 17, 9),
+                                   (300, 260, 31), (2049, 2177, 129), (129, 4097, 16)])
 @pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
 def test_native_fp64_gemm(lib, ta, tb, shape):
     g, h = lib
@@ -418,6 +419,10 @@ def test_native_fp64_gemm(lib, ta, tb, shape):
     exact = ex.exact_entries(A, B, idx, 1.5, 0.5, Cin)
     den = ex.bound_denominator(A, B, idx, 1.5, 0.5, Cin)
     assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
+    # every entry (edge tiles included) against the host product: both sides are within k*2^-53 of the exact value
+    full = 1.5 * (A @ B) + 0.5 * Cin
+    slack = 2.0 * (k + 2) * 2.0 ** -53 * (1.5 * (np.abs(A) @ np.abs(B)) + 0.5 * np.abs(Cin))
+    assert np.all(np.abs(got - full) <= slack)
 
 
 @pytest.mark.parametrize("seed", range(16))
