@@ -370,6 +370,10 @@ oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, in
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Workspace w = bind(workspace, p, L);
     StageClock clk(h, st, timed);
+    // what the native GEMM may use for the partial products of a k split: the slice planes, the
+    // aggregated products and the raw sums, none of which a call that falls back reads or writes
+    void* const f64_scratch = w.As;
+    const size_t f64_scratch_bytes = size_t(reinterpret_cast<uint8_t*>(w.tile_span) - reinterpret_cast<uint8_t*>(w.As));
 
     if (k == 0 || alpha == 0.0) {
         // BLAS convention: nothing to multiply
@@ -386,7 +390,7 @@ oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, in
     if (opts->mode == OZ_NATIVE) {
         launch_verdict(st, w, p, *opts, h->hm, 0, result);
         for (int s = 0; s <= 5; ++s) clk.done(s);
-        launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+        launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, f64_scratch, f64_scratch_bytes);
         clk.done(6);
         return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
     }
@@ -399,7 +403,7 @@ oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, in
         if (emulation_slower(h->hm, s_min, m, n, k)) {
             launch_verdict(st, w, p, *opts, h->hm, 3, result);
             for (int s = 0; s <= 5; ++s) clk.done(s);
-            launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+            launch_dgemm_f64(st, nullptr, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, f64_scratch, f64_scratch_bytes);
             clk.done(6);
             return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
         }
@@ -422,7 +426,7 @@ oz_status_t dgemm_impl(oz_handle_t h, void* stream, char transa, char transb, in
     clk.done(4);
     launch_recompose(st, w, p, alpha, beta, C, ldc);
     clk.done(5);
-    if (guarded) launch_dgemm_f64(st, w.rec, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+    if (guarded) launch_dgemm_f64(st, w.rec, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, f64_scratch, f64_scratch_bytes);
     clk.done(6);
     return hipGetLastError() == hipSuccess ? OZ_OK : OZ_ERR_HIP;
 }

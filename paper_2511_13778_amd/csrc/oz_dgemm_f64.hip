@@ -103,7 +103,7 @@ template <bool A_ROWS_CONTIG, bool B_ROWS_CONTIG, int MODE, int T>
 __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     const Record* rec, int64_t m, int64_t n, int64_t k, double alpha, const double* __restrict__ A,
     int64_t a_sr, int64_t a_sl, const double* __restrict__ B, int64_t b_sr, int64_t b_sl, double beta,
-    double* __restrict__ C, int64_t ldc, int ntm, int ntn) {
+    double* __restrict__ C, int64_t ldc, int ntm, int ntn, int zsplit, int64_t kpart, double* __restrict__ partial) {
     constexpr bool EDGE = MODE == 2;                       // bounds-checked loads in the K loop
     constexpr bool RAGGED = MODE != 0;                     // bounds-checked stores of C
     constexpr bool A_PER_Q = MODE == 1 && !A_ROWS_CONTIG, B_PER_Q = MODE == 1 && !B_ROWS_CONTIG;
@@ -118,12 +118,15 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
     // Workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous range of a tile
     // order in which 64 consecutive tiles (what an XCD runs at a time: 32 CUs, two workgroups each)
     // form an 8 x 8 block, so they share 16 panels in that XCD's L2.
-    int ti, tj;
+    // With a k split (zsplit > 1) a work unit is (tile, part of the k range), ordered part by part.
+    int ti, tj, z;
     {
-        const int total = ntm * ntn;
+        const int tiles = ntm * ntn, total = tiles * zsplit;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
         const int per = total >> 3, rem = total & 7;
-        const int lin = xcd * per + min(xcd, rem) + slot;
+        const int unit = xcd * per + min(xcd, rem) + slot;
+        z = unit / tiles;
+        const int lin = unit - z * tiles;
         constexpr int GW = 8;
         const int panel = lin / (GW * ntm);
         const int in_panel = lin - panel * GW * ntm;
@@ -132,6 +135,15 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
         tj = panel * GW + in_panel % w;
     }
     const int64_t i0 = int64_t(ti) * T, j0 = int64_t(tj) * T;
+    // this unit's k range: part 0 is [0, k - (zsplit-1)*kpart) and carries k mod 16, the others have kpart
+    // (a multiple of 16) each; from here on A, B and k describe that range alone
+    if (zsplit > 1) {
+        const int64_t k0 = k - int64_t(zsplit - 1) * kpart;
+        const int64_t kb = z == 0 ? 0 : k0 + int64_t(z - 1) * kpart;
+        A += kb * a_sl;
+        B += kb * b_sl;
+        k = z == 0 ? k0 : kpart;
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wi = wave & 1, wj = wave >> 1;
 
@@ -246,6 +258,18 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
 #undef OZ_DG_MFMA
 
     // result register r of tile (fj, fi): j = fj*16 + 4*r + lane/16, i = fi*16 + lane%16
+    if (zsplit > 1) {
+        // partial product of this part of the k range: tile (ti, tj) of part z, T x T doubles, i contiguous
+        double* dst = partial + ((int64_t(z) * ntn + tj) * ntm + ti) * (T * T);
+#pragma unroll
+        for (int fj = 0; fj < MT; ++fj)
+#pragma unroll
+            for (int fi = 0; fi < MT; ++fi)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    dst[(wj * WT + fj * 16 + 4 * r + (lane >> 4)) * T + wi * WT + fi * 16 + (lane & 15)] = acc[fj][fi][r];
+        return;
+    }
 #pragma unroll
     for (int fj = 0; fj < MT; ++fj)
 #pragma unroll
@@ -262,9 +286,28 @@ __global__ __launch_bounds__(256, 2) void dgemm_f64_kernel(
             }
 }
 
+// C = alpha * (sum of the parts' partial products, in the order of the parts) + beta * C
+template <int T>
+__global__ __launch_bounds__(256) void dgemm_f64_reduce_kernel(const Record* rec, int64_t m, int64_t n, double alpha,
+                                                               double beta, double* __restrict__ C, int64_t ldc, int ntm,
+                                                               int ntn, int zsplit, const double* __restrict__ partial) {
+    if (rec && !rec->res.fallback) return;
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t j = blockIdx.y;
+    if (i >= m) return;
+    const int64_t ti = i / T, tj = j / T;
+    const double* src = partial + (tj * ntm + ti) * (T * T) + (j - tj * T) * T + (i - ti * T);
+    const int64_t part_stride = int64_t(ntn) * ntm * (T * T);
+    double sum = src[0];
+    for (int z = 1; z < zsplit; ++z) sum = __dadd_rn(sum, src[z * part_stride]);
+    double out = __dmul_rn(alpha, sum);
+    if (beta != 0.0) out = __dadd_rn(out, __dmul_rn(beta, C[j * ldc + i]));
+    C[j * ldc + i] = out;
+}
+
 void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64_t m, int64_t n, int64_t k,
                       double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
-                      double* C, int64_t ldc) {
+                      double* C, int64_t ldc, void* scratch, size_t scratch_bytes) {
     // op(A)(i,l): N -> A[i + l*lda] (rows contiguous), T -> A[l + i*lda]
     // op(B)(l,j): N -> B[l + j*ldb] (k contiguous),    T -> B[j + l*ldb] (rows contiguous)
     const int64_t a_sr = ta ? lda : 1, a_sl = ta ? 1 : lda;
@@ -274,21 +317,39 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
     const int64_t tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
     int device = 0, num_cu = 256;
     if (hipGetDevice(&device) == hipSuccess) (void)hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, device);
-    const bool small = tiles128 < num_cu;
-    const int T = small ? 64 : 128;
-    const int ntm = int((m + T - 1) / T), ntn = int((n + T - 1) / T);
-    const dim3 grid(unsigned(ntm) * unsigned(ntn)), block(256);
     // the interior path keeps every offset inside a K step of a tile in 32 bits (a lane's own: at most
     // 15 leading dimensions plus a row of the tile; its elements: up to 7 x 16 leading dimensions
     // further on; in bytes); operands cut out of a very large parent matrix take the bounds-checked
     // path, which indexes in 64 bits
     const int64_t ld_max = lda > ldb ? lda : ldb;
     const bool wide_ld = (128 * ld_max + 256) * 8 >= (int64_t(1) << 32);
+    // Few tiles and a long k (a skinny or small output): with scratch memory at hand, the k range is split
+    // over zsplit workgroups per 128 x 128 tile so that the two workgroup slots of every CU are filled;
+    // the parts leave partial products in the scratch memory and a second kernel adds them in the order
+    // of the parts (deterministic) and applies alpha and beta.  Each part gets at least 512 of k.
+    int zsplit = 1;
+    int64_t kpart = 0;
+    if (tiles128 < num_cu && !wide_ld && scratch != nullptr) {
+        int64_t z = (2 * int64_t(num_cu)) / tiles128;
+        if (z > 16) z = 16;
+        if (z > k / 512) z = k / 512;
+        const int64_t fit = int64_t(scratch_bytes / (size_t(tiles128) * 128 * 128 * 8));
+        if (z > fit) z = fit;
+        if (z >= 2) {
+            zsplit = int(z);
+            kpart = k / z / kDK * kDK;
+        }
+    }
+    const bool small = tiles128 < num_cu && zsplit == 1;
+    const int T = small ? 64 : 128;
+    const int ntm = int((m + T - 1) / T), ntn = int((n + T - 1) / T);
+    const dim3 grid(unsigned(ntm) * unsigned(ntn) * unsigned(zsplit)), block(256);
+    double* partial = static_cast<double*>(scratch);
     // k < 16: the fast loads always fetch a full K step, which such a matrix does not have
     const int mode = (wide_ld || k < kDK) ? 2 : (((m % T) || (n % T) || (k % kDK)) ? 1 : 0);
 #define OZ_DG_M(AC, BC, MODE, TT)                                                                              \
     hipLaunchKernelGGL((dgemm_f64_kernel<AC, BC, MODE, TT>), grid, block, 0, st, rec, m, n, k, alpha, A, a_sr, \
-                       a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn)
+                       a_sl, B, b_sr, b_sl, beta, C, ldc, ntm, ntn, zsplit, kpart, partial)
 #define OZ_DG_T(AC, BC, TT)                                                                                    \
     {                                                                                                          \
         if (mode == 2) OZ_DG_M(AC, BC, 2, TT);                                                                 \
@@ -306,6 +367,12 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
 #undef OZ_DG_T
 #undef OZ_DG_M
 #undef OZ_DG
+    if (zsplit > 1) {
+        const unsigned gx = unsigned((m + 255) / 256);
+        // n < 128 * 256 here (fewer than 256 tiles of 128 columns), so n fits grid.y
+        hipLaunchKernelGGL((dgemm_f64_reduce_kernel<128>), dim3(gx, unsigned(n)), dim3(256), 0, st, rec, m, n, alpha, beta,
+                           C, ldc, ntm, ntn, zsplit, partial);
+    }
 }
 
 }  // namespace oz

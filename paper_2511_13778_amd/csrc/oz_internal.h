@@ -109,10 +109,13 @@ void launch_slice(hipStream_t st, const double* X, int64_t stride_r, int64_t str
 void launch_gemm_i8(hipStream_t st, const Workspace& w, const Problem& p);
 void launch_recompose(hipStream_t st, const Workspace& w, const Problem& p, double alpha,
                       double beta, double* C, int64_t ldc);
-// rec == nullptr: run unconditionally; otherwise run only when rec->res.fallback != 0
+// rec == nullptr: run unconditionally; otherwise run only when rec->res.fallback != 0.
+// scratch (may be nullptr): device memory the kernel may use for partial products when it splits the
+// k range of a product with few tiles; nothing else may use it while the GEMM runs
 void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64_t m, int64_t n,
                       int64_t k, double alpha, const double* A, int64_t lda, const double* B,
-                      int64_t ldb, double beta, double* C, int64_t ldc);
+                      int64_t ldb, double beta, double* C, int64_t ldc, void* scratch = nullptr,
+                      size_t scratch_bytes = 0);
 void launch_scale_c(hipStream_t st, int64_t m, int64_t n, double beta, double* C, int64_t ldc);
 // complex product by the 4M method: split an interleaved complex matrix into planar parts (conj negates
 // the imaginary part), and combine the planar product with alpha, beta and the interleaved C

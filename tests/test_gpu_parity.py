@@ -406,7 +406,9 @@ def test_heuristic_after_the_esc(lib):
 
 # 64-tiles: ragged and interior; 128-tiles (at least 256 of them): ragged and interior
 @pytest.mark.parametrize("shape", [(200, 150, 333), (256, 384, 512), (2100, 2050, 50), (2048, 2048, 64), (33, 17, 9),
-                                   (300, 260, 31), (2049, 2177, 129), (129, 4097, 16)])
+                                   (300, 260, 31), (2049, 2177, 129), (129, 4097, 16),
+                                   # few tiles and a long k: the k range is split over several workgroups per tile
+                                   (256, 300, 20000), (1000, 900, 4100), (1024, 1024, 8192), (128, 128, 1024)])
 @pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
 def test_native_fp64_gemm(lib, ta, tb, shape):
     g, h = lib
@@ -423,6 +425,29 @@ def test_native_fp64_gemm(lib, ta, tb, shape):
     full = 1.5 * (A @ B) + 0.5 * Cin
     slack = 2.0 * (k + 2) * 2.0 ** -53 * (1.5 * (np.abs(A) @ np.abs(B)) + 0.5 * np.abs(Cin))
     assert np.all(np.abs(got - full) <= slack)
+
+
+def test_native_k_split_is_reproducible_and_serves_the_guarded_call(lib):
+    # a product with few tiles and a long k falls back on a NaN: the native GEMM splits k over several
+    # workgroups per tile and adds the parts in a fixed order, so the result is the same on every run and
+    # equals the host product within the bound wherever the NaN does not reach
+    g, h = lib
+    m, n, k = 300, 260, 9000
+    A, B = wl.lognormal_spread(m, k, n, 0.5, seed=44)
+    A[17, 4000] = np.nan
+    outs = []
+    for _ in range(2):
+        got, _, res = run_gpu(g, h, A, B, 1.0, 0.0, None, "N", "N", mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200,
+                              heuristic=0)
+        assert (res.fallback, res.reason) == (1, oz.REASON_INFNAN)
+        outs.append(got)
+    assert np.array_equal(np.isnan(outs[0]), np.isnan(outs[1]))
+    assert np.array_equal(np.nan_to_num(outs[0]), np.nan_to_num(outs[1]))
+    assert np.all(np.isnan(outs[0][17, :])) and not np.isnan(np.delete(outs[0], 17, axis=0)).any()
+    rows = np.array([r for r in range(m) if r != 17])
+    full = A[rows] @ B
+    slack = 2.0 * (k + 2) * 2.0 ** -53 * (np.abs(A[rows]) @ np.abs(B))
+    assert np.all(np.abs(outs[0][rows] - full) <= slack)
 
 
 @pytest.mark.parametrize("seed", range(16))
