@@ -108,3 +108,39 @@ def test_only_the_allowed_places_use_the_oracle():
         if name.endswith(".py"):
             src = open(os.path.join(ROOT, "oracle", name)).read()
             assert "paper_2511_13778_amd" not in src and "ctypes" not in src, name
+
+
+def test_headers_are_plain_c_and_struct_layouts_match_the_binding(tmp_path):
+    # the boundary is a C ABI: both headers must compile as C99 on their own, and the structs the Python
+    # binding mirrors must have the sizes and field offsets the C compiler gives them
+    import ctypes as C
+    import subprocess
+    from paper_2511_13778_amd import ozdgemm as g
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "ozdgemm.h"
+#include "ozprobe.h"
+int main(void) {
+    printf("opts %zu %zu %zu\n", sizeof(oz_opts_t), offsetof(oz_opts_t, esc_block), offsetof(oz_opts_t, tile_slices));
+    printf("result %zu %zu %zu\n", sizeof(oz_result_t), offsetof(oz_result_t, slices_min), offsetof(oz_result_t, pair_tiles));
+    printf("heur %zu %zu\n", sizeof(oz_heuristic_t), offsetof(oz_heuristic_t, fixed_ns));
+    printf("layout %zu %zu %zu %zu\n", sizeof(oz_layout_t), offsetof(oz_layout_t, nkb), offsetof(oz_layout_t, off_T),
+           offsetof(oz_layout_t, total_bytes));
+    printf("consts %d %d %u\n", OZ_NUM_STAGES, OZ_BATCH_LANES, (unsigned)OZ_STATIC_SCRATCH_BYTES);
+    return 0;
+}
+''')
+    exe = tmp_path / "abi"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), str(src), "-o", str(exe)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    out = dict((ln.split()[0], [int(v) for v in ln.split()[1:]]) for ln in subprocess.run([str(exe)], capture_output=True, text=True).stdout.splitlines())
+    assert out["opts"] == [C.sizeof(g.oz_opts_t), g.oz_opts_t.esc_block.offset, g.oz_opts_t.tile_slices.offset]
+    assert out["result"] == [C.sizeof(g.oz_result_t), g.oz_result_t.slices_min.offset, g.oz_result_t.pair_tiles.offset]
+    assert out["heur"] == [C.sizeof(g.oz_heuristic_t), g.oz_heuristic_t.fixed_ns.offset]
+    assert out["layout"] == [C.sizeof(g.oz_layout_t), g.oz_layout_t.nkb.offset, g.oz_layout_t.off_T.offset,
+                             g.oz_layout_t.total_bytes.offset]
+    assert out["consts"] == [g.OZ_NUM_STAGES, 4, 256 << 20]
