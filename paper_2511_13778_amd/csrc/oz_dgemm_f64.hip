@@ -335,7 +335,10 @@ void launch_dgemm_f64(hipStream_t st, const Record* rec, bool ta, bool tb, int64
         if (z > k / 512) z = k / 512;
         const int64_t fit = int64_t(scratch_bytes / (size_t(tiles128) * 128 * 128 * 8));
         if (z > fit) z = fit;
-        if (z >= 2) {
+        // A 64 x 64 tile's K step takes about 0.3 of a 128 x 128 tile's, so against the unsplit 64 x 64 path a
+        // split pays from four parts on, or from two if the parts give every CU a workgroup (measured:
+        // 512 x 512 x 8192 with 5 parts 0.20 ms against 0.40 ms; 1024^3 with 2 parts is slower than unsplit)
+        if (z >= 4 || (z >= 2 && z * tiles128 >= num_cu)) {
             zsplit = int(z);
             kpart = k / z / kDK * kDK;
         }
