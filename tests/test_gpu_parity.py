@@ -434,6 +434,40 @@ def test_native_fp64_gemm(lib, ta, tb, shape):
     assert np.all(np.abs(got - full) <= slack)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_randomized_native_shapes(lib, seed):
+    # the FP64 fallback over drawn shapes (small with a long k, tall, wide, short k), transposes, scalars and
+    # leading dimensions, reached both as OZ_NATIVE (small workspace) and through the guard on an Inf in A
+    # (workspace of the default mode, so skinny products split k): every finite entry of the host product is
+    # matched inside the bound, every other entry is Inf or NaN
+    g, h = lib
+    rng = np.random.default_rng(31000 + seed)
+    kind = seed % 4
+    if kind == 0:
+        m, n, k = int(rng.integers(1, 600)), int(rng.integers(1, 600)), int(rng.integers(1, 9000))
+    elif kind == 1:
+        m, n, k = int(rng.integers(1, 3000)), int(rng.integers(1, 300)), int(rng.integers(500, 5000))
+    elif kind == 2:
+        m, n, k = int(rng.integers(1, 300)), int(rng.integers(1, 3000)), int(rng.integers(500, 5000))
+    else:
+        m, n, k = int(rng.integers(100, 2200)), int(rng.integers(100, 2200)), int(rng.integers(1, 700))
+    A, B, Cin = rng.standard_normal((m, k)), rng.standard_normal((k, n)), rng.standard_normal((m, n))
+    alpha, beta = float(rng.choice([1.0, -1.5, 0.3])), float(rng.choice([0.0, 1.0, 0.5]))
+    ta, tb = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+    guarded = bool(seed & 4)
+    opt = dict(mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200, heuristic=0) if guarded else dict(mode=g.OZ_NATIVE)
+    if guarded:
+        A[int(rng.integers(m)), int(rng.integers(k))] = np.inf
+    got, _, res = run_gpu(g, h, A, B, alpha, beta, Cin if beta else None, ta, tb, pad=int(rng.integers(0, 3)), **opt)
+    assert (res.fallback, res.reason) == (1, oz.REASON_INFNAN if guarded else oz.REASON_NATIVE)
+    with np.errstate(all="ignore"):
+        want = alpha * (A @ B) + (beta * Cin if beta else 0.0)
+        slack = 2.0 * (k + 2) * 2.0 ** -53 * (abs(alpha) * (np.abs(A) @ np.abs(B)) + abs(beta) * np.abs(Cin))
+        fin = np.isfinite(want) & np.isfinite(slack)
+    assert np.all(np.abs(got[fin] - want[fin]) <= slack[fin])
+    assert not np.isfinite(got[~fin]).any()
+
+
 def test_native_k_split_is_reproducible_and_serves_the_guarded_call(lib):
     # a product with few tiles and a long k falls back on a NaN: the native GEMM splits k over several
     # workgroups per tile and adds the parts in a fixed order, so the result is the same on every run and
