@@ -468,14 +468,16 @@ def test_randomized_native_shapes(lib, seed):
     assert not np.isfinite(got[~fin]).any()
 
 
-def test_native_k_split_is_reproducible_and_serves_the_guarded_call(lib):
-    # a product with few tiles and a long k falls back on a NaN: the native GEMM splits k over several
-    # workgroups per tile and adds the parts in a fixed order, so the result is the same on every run and
-    # equals the host product within the bound wherever the NaN does not reach
+@pytest.mark.parametrize("shape", [(300, 260, 9000), (2304, 2200, 1100)])
+def test_native_k_split_is_reproducible_and_serves_the_guarded_call(lib, shape):
+    # a product falls back on a NaN: the native GEMM splits k over several workgroups per tile (few tiles and a
+    # long k; or 18 x 18 tiles, 1.27 per CU, where two parts per tile shorten the last round) and adds the parts
+    # in a fixed order, so the result is the same on every run and equals the host product within the bound
+    # wherever the NaN does not reach
     g, h = lib
-    m, n, k = 300, 260, 9000
+    m, n, k = shape
     A, B = wl.lognormal_spread(m, k, n, 0.5, seed=44)
-    A[17, 4000] = np.nan
+    A[17, k // 2] = np.nan
     outs = []
     for _ in range(2):
         got, _, res = run_gpu(g, h, A, B, 1.0, 0.0, None, "N", "N", mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200,
