@@ -252,8 +252,9 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
         }
         if (prev >= 0 && prev != device) (void)hipSetDevice(prev);
     }
-    // measured on MI355X at 8192^3: slice GEMM 2.65 POP/s, native FP64 GEMM 66-72 TFLOP/s (the lower figure, reached at 4096^3, is used), streaming
-    // kernels about 4 TB/s, launch overhead of the ten kernels of a call
+    // measured on MI355X: slice GEMM 2.6-2.9 POP/s at 8192^3 (2.65 is used), native FP64 GEMM 55-75 TFLOP/s
+    // between 2304^3 and 8192^3 (66 is used), streaming kernels about 4 TB/s, launch overhead of the ten
+    // kernels of a call
     h->hm.int8_ops_per_ns = 2650000;
     h->hm.fp64_flops_per_ns = 66000;
     h->hm.bytes_per_ns = 4000;
