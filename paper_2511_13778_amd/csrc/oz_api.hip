@@ -130,7 +130,7 @@ void make_layout(const Problem& p, oz_layout_t& L) {
     off = align_up(off + size_t(p.nkb) * p.s_cap * p.raw_slots * kTile * kTile * 4);
     const size_t tiles = size_t(p.mp / kTile) * size_t(p.np / kTile);
     off = align_up(off + tiles * 4);                 // tile_span (not part of the published layout)
-    L.off_tileS = off; off = align_up(off + tiles * 4);
+    L.off_tileS = off; off = align_up(off + tiles * 8);   // slice counts, then the order the tiles are dealt in
     L.total_bytes = off;
 }
 

@@ -78,7 +78,8 @@ struct Workspace {
     int32_t* raw;          // [nkb][s_cap][raw_slots][kTile][kTile]  unaggregated sums of the tiles whose k range is split
                            //                                 over several workgroups (integer atomics), tile-local [j][i]
     int32_t* tile_span;    // [np/kTile][mp/kTile] largest coarsened span of the block's dot products (atomicMax)
-    int32_t* tile_S;       // [np/kTile][mp/kTile] slice count of the block (per-tile mode)
+    int32_t* tile_S;       // [np/kTile][mp/kTile] slice count of the block (per-tile mode), followed by as many
+                           // entries again: the order in which the slice GEMM deals the tiles to its workgroups
 };
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
