@@ -112,13 +112,19 @@ def localised(torch, g, h, reps):
     n = 8192
     lines = ["# m = n = k = %d, +-U(1,2) entries, rows 3000..3099 of A with a %%d-bit exponent span against every third column;"
              " alpha = 1, beta = 0; %d timed calls per entry" % (n, reps),
-             "spread | mode                      S_max S_min pair products of 256x256 blocks   ms      TFLOP/s  x vendor FP64"]
-    for spread in (24, 40, 60):
+             "# 'cols': the transposed product, i.e. the hard region is a band of columns of C",
+             "spread | mode                      S_max S_min pair products of 256x256 blocks   ms      TFLOP/s  x vendor FP64 x own FP64"]
+    # the last case transposes the product (A <- B^T, B <- A^T): the same hard region as a band of columns of C
+    for spread, columns in ((24, False), (40, False), (60, False), (24, True)):
         A, B = wl.wide_rows(n, n, n, seed=11, row_lo=3000, row_hi=3100, spread=spread)
+        if columns:
+            A, B = np.ascontiguousarray(B.T), np.ascontiguousarray(A.T)
         dA, dB = g.to_colmajor(A), g.to_colmajor(B)
         del A, B
         dC = torch.zeros((n, n), dtype=torch.float64, device="cuda")
         t_ven = timed(torch, lambda: torch.matmul(dB, dA), 3)
+        t_own = timed(torch, lambda: h.native_dgemm(st, "N", "N", n, n, n, 1.0, dA.data_ptr(), n, dB.data_ptr(), n, 0.0,
+                                                    dC.data_ptr(), n), 3)
         for name, opt in (("dynamic, one count", dict(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0, tile_slices=0)),
                           ("dynamic, per-block counts", dict(mode=g.OZ_DYNAMIC, max_bits=200, heuristic=0, tile_slices=1)),
                           ("as shipped (heuristic on)", None)):
@@ -128,7 +134,8 @@ def localised(torch, g, h, reps):
             r = gm.result()
             what = "native (reason %d)" % r.reason if r.fallback else "%-5d %-5d %d" % (r.slices_used, r.slices_min, r.pair_tiles)
             lines[0] = lines[0]
-            lines.append("%-6d | %-25s %-40s %-7.2f %-8.1f %.2f" % (spread, name, what, ms, 2.0 * n ** 3 / ms * 1e-9, t_ven / ms))
+            lines.append("%-6s | %-25s %-40s %-7.2f %-8.1f %-13.2f %.2f" % (("%d cols" % spread) if columns else str(spread), name, what, ms,
+                                                                          2.0 * n ** 3 / ms * 1e-9, t_ven / ms, t_own / ms))
             del gm
         del dA, dB, dC
         torch.cuda.empty_cache()

@@ -234,7 +234,8 @@ oz_status_t oz_zgemm(oz_handle_t handle, void* stream, char transa, char transb,
  *   L    int8 [nkb][S_cap-1][np/4][mp][4]   balanced digit L_d in [-128,127], d >= 1, of element (i,j) at
  *                               (((kb*(S_cap-1) + d-1)*(np/4) + j/4)*mp + i)*4 + j%4
  *   tileS int32[np/256][mp/256]  slice count of block (ti, tj) of C at tj*(mp/256) + ti (written only
- *                               with tile_slices in OZ_DYNAMIC mode)
+ *                               with tile_slices in OZ_DYNAMIC mode); the same number of int32 follows it: the
+ *                               order in which the slice GEMM dealt the blocks to its workgroups
  * mp, np = m, n rounded up to 256; kp = k rounded up to 128; kblk = k-block length for S_cap. */
 typedef struct {
     int64_t mp, np, kp, s_cap, nkb, kblk;

@@ -276,6 +276,15 @@ class Gemm:
         nti, ntj = L.mp // 256, L.np // 256
         return self._view(L.off_tileS, nti * ntj * 4, torch.int32).view(ntj, nti).cpu().numpy().T.copy()
 
+    def tile_order(self):
+        """The order in which the slice GEMM dealt the blocks of C to its workgroups in the last per-block call:
+        entry p = index, in the GEMM's block order, of the block that ran at position p (stored behind the
+        slice counts)."""
+        import torch
+        L = self.L
+        tiles = (L.mp // 256) * (L.np // 256)
+        return self._view(L.off_tileS + tiles * 4, tiles * 4, torch.int32).cpu().numpy().copy()
+
     # views of the intermediates in the workspace (for parity tests)
     def _view(self, off, nbytes, dtype):
         return self.ws[off:off + nbytes].view(dtype)

@@ -616,6 +616,37 @@ def test_per_tile_slice_counts(lib, ta, tb, seed):
     assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
 
 
+def test_per_tile_counts_with_the_tiles_dealt_by_slice_count(lib):
+    # 16 x 16 blocks of C (one full round of the slice GEMM, so its tiles are sorted by slice count and dealt
+    # to the XCDs in turn), the difficult dot products in two block columns: whatever order the blocks run in,
+    # record, per-block counts and every entry of C are the oracle's
+    g, h = lib
+    m = n = 4096
+    k = 192
+    A0, B0 = wl.wide_rows(n, k, m, seed=13, row_lo=1000, row_hi=1040, spread=20)
+    A, B = np.ascontiguousarray(B0.T), np.ascontiguousarray(A0.T)          # hard columns of C instead of hard rows
+    got, gm, res = run_gpu(g, h, A, B, 1.0, 0.0, None, "N", "N", mode=g.OZ_DYNAMIC, target_bits=53, max_bits=200,
+                           heuristic=0, tile_slices=1)
+    tr = oz.emulated_dgemm(A, B, 1.0, 0.0, None, mode=oz.MODE_DYNAMIC, target_bits=53, max_bits=200, per_tile=True)
+    v = tr.verdict
+    assert (res.fallback, res.reason, res.slices_used, res.esc, res.required_bits, res.infnan, res.slices_min,
+            res.pair_tiles) == (v.fallback, v.reason, v.slices_used, v.esc, v.required_bits, v.infnan, v.slices_min,
+                                v.pair_tiles)
+    assert v.slices_min < v.slices_used
+    np.testing.assert_array_equal(gm.tile_slice_counts(), tr.S_tile)
+    heavy = np.argwhere(tr.S_tile == v.slices_used)
+    assert set(heavy[:, 1].tolist()) == {3, 4} and len(heavy) == 32         # two block columns of sixteen blocks
+    np.testing.assert_array_equal(got, tr.C)
+    # the order table is a permutation of the blocks, and the 32 heavy blocks are the first round of the first XCD
+    # (positions 0..31 of the 256: the sorted sequence is dealt in groups of 32, group g to XCD g % 8)
+    order = gm.tile_order()
+    assert sorted(order.tolist()) == list(range(256))
+    first_round = order[:32]
+    # block order of the GEMM: panels of 8 block columns, inside a panel row by row
+    tj_of = lambda lin: (lin // (8 * 16)) * 8 + (lin % (8 * 16)) % 8
+    assert {tj_of(int(v)) for v in first_round} == {3, 4}
+
+
 def test_per_tile_cost_model_keeps_a_localised_hard_region_emulated(lib):
     # With one slice count for all of C the cost model sends this input to the native GEMM (the worst
     # block's count applied everywhere is too slow); with per-block counts the mean pair count decides,
