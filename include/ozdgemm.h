@@ -97,7 +97,7 @@ typedef struct {
 /* Cost model of the run-time heuristic (section "Heuristic run time Selection"); integer
  * arithmetic so that host, device and any checker agree bit for bit:
  *   t_emu = fixed_ns + (2mnk / int8_ops_per_ns) * S(S+1)/2
- *           + ((8+S)(mk+kn) + (8S+16)mn) / bytes_per_ns,      t_f64 = 2mnk / fp64_flops_per_ns,
+ *           + ((16+S)(mk+kn) + (2S+22)mn) / bytes_per_ns,     t_f64 = 2mnk / fp64_flops_per_ns,
  * emulation is "slower" when t_emu > t_f64.  With tile_slices the factor S(S+1)/2 is replaced by the
  * mean pair count per 256 x 256 block of C, rounded up; S in the streaming term is the largest S_T. */
 typedef struct {

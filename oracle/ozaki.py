@@ -215,17 +215,20 @@ class HeuristicModel:
     """Integer cost model for "emulation slower than FP64?" (parity unpinned: own constants).
     Rates in operations per nanosecond, fixed cost in nanoseconds, bandwidth in bytes/ns."""
     int8_ops_per_ns: int = 2650000
-    fp64_flops_per_ns: int = 66000
+    fp64_flops_per_ns: int = 74000
     bytes_per_ns: int = 4000
     fixed_ns: int = 60000
 
     def emulation_slower(self, S: int, m: int, n: int, k: int, pairs: int | None = None) -> bool:
         """S: slice count (sets the streaming cost); pairs: slice-pair products per tile of C,
-        S(S+1)/2 unless the tiles of C take different slice counts (then the mean, rounded up)."""
+        S(S+1)/2 unless the tiles of C take different slice counts (then the mean, rounded up).
+        Streamed bytes: the scan reads 8 and the slicing reads 8 and writes S per operand element; per
+        element of C the aggregated anti-diagonal sums (4 + (S-1) bytes) are written once and read
+        once, and C is read and written."""
         flops = 2 * m * n * k
         if pairs is None:
             pairs = S * (S + 1) // 2
-        stream = (8 + S) * (m * k + k * n) + (8 * S + 16) * m * n
+        stream = (16 + S) * (m * k + k * n) + (2 * S + 22) * m * n
         t_emu = self.fixed_ns + (flops // self.int8_ops_per_ns) * pairs + stream // self.bytes_per_ns
         t_f64 = flops // self.fp64_flops_per_ns
         return t_emu > t_f64

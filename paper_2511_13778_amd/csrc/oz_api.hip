@@ -59,7 +59,9 @@ bool valid_opts(const oz_opts_t& o) {
 bool emulation_slower(const oz_heuristic_t& hm, int S, int64_t m, int64_t n, int64_t k) {
     const int64_t flops = 2 * m * n * k;
     const int64_t pairs = int64_t(S) * (S + 1) / 2;
-    const int64_t stream = (8 + S) * (m * k + k * n) + (8 * int64_t(S) + 16) * m * n;
+    // bytes the streaming stages move: scan 8, slicing 8 + S per operand element; per element of C the slice GEMM
+    // writes and the recomposition reads 4 + (S - 1) (leading word and digits), and C is read and written
+    const int64_t stream = (16 + S) * (m * k + k * n) + (2 * int64_t(S) + 22) * m * n;
     const int64_t t_emu = hm.fixed_ns + (flops / hm.int8_ops_per_ns) * pairs + stream / hm.bytes_per_ns;
     const int64_t t_f64 = flops / hm.fp64_flops_per_ns;
     return t_emu > t_f64;
@@ -253,10 +255,10 @@ oz_status_t oz_create(oz_handle_t* handle, int device) {
         if (prev >= 0 && prev != device) (void)hipSetDevice(prev);
     }
     // measured on MI355X: slice GEMM 2.6-2.9 POP/s at 8192^3 (2.65 is used), native FP64 GEMM 55-75 TFLOP/s
-    // between 2304^3 and 8192^3 (66 is used), streaming kernels about 4 TB/s, launch overhead of the ten
+    // between 2304^3 and 8192^3 (74, its rate where emulation competes, is used), streaming kernels about 4 TB/s, launch overhead of the ten
     // kernels of a call
     h->hm.int8_ops_per_ns = 2650000;
-    h->hm.fp64_flops_per_ns = 66000;
+    h->hm.fp64_flops_per_ns = 74000;
     h->hm.bytes_per_ns = 4000;
     h->hm.fixed_ns = 60000;
     h->prof_calls = 0;

@@ -339,7 +339,7 @@ __global__ void verdict_kernel(Record* rec, oz_opts_t o, oz_heuristic_t hm, int 
                 const int64_t pairs = per_tile ? int64_t((rec->pair_acc + (unsigned long long)(tiles) - 1) /
                                                          (unsigned long long)(tiles))
                                                : int64_t(S) * (S + 1) / 2;
-                const int64_t stream = (8 + S) * (m * k + k * n) + (8 * int64_t(S) + 16) * m * n;
+                const int64_t stream = (16 + S) * (m * k + k * n) + (2 * int64_t(S) + 22) * m * n;
                 const int64_t t_emu = hm.fixed_ns + (flops / hm.int8_ops_per_ns) * pairs + stream / hm.bytes_per_ns;
                 const int64_t t_f64 = flops / hm.fp64_flops_per_ns;
                 slower = t_emu > t_f64;

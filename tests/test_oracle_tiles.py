@@ -160,7 +160,7 @@ def test_heuristic_closed_forms_and_monotonicity():
     # rational re-statement of the model at one point (integer floors only move it by < 3 ns)
     S, m, n, k = 8, 6000, 5000, 7000
     t_emu = Fraction(hm.fixed_ns) + Fraction(2 * m * n * k, hm.int8_ops_per_ns) * 36 + \
-        Fraction((8 + S) * (m * k + k * n) + (8 * S + 16) * m * n, hm.bytes_per_ns)
+        Fraction((16 + S) * (m * k + k * n) + (2 * S + 22) * m * n, hm.bytes_per_ns)
     t_f64 = Fraction(2 * m * n * k, hm.fp64_flops_per_ns)
     assert abs(t_emu - t_f64) > 40                     # the decision is not a rounding accident
     assert hm.emulation_slower(S, m, n, k) == (t_emu > t_f64)
