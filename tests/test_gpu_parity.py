@@ -616,12 +616,13 @@ def test_per_tile_slice_counts(lib, ta, tb, seed):
     assert ex.gradeA_ratio(np.array([got[i, j] for i, j in idx]), exact, den, k) <= 1.0
 
 
-def test_per_tile_counts_with_the_tiles_dealt_by_slice_count(lib):
-    # 16 x 16 blocks of C (one full round of the slice GEMM, so its tiles are sorted by slice count and dealt
-    # to the XCDs in turn), the difficult dot products in two block columns: whatever order the blocks run in,
-    # record, per-block counts and every entry of C are the oracle's
+@pytest.mark.parametrize("m,n", [(4096, 4096), (4352, 4100)])
+def test_per_tile_counts_with_the_tiles_dealt_by_slice_count(lib, m, n):
+    # 16 x 16 blocks of C (one full round of the slice GEMM) or 17 x 17 (a full round and a k-split launch for
+    # the 33 blocks left over): the blocks are sorted by slice count and dealt to the XCDs in turn.  The difficult
+    # dot products lie in two block columns; whatever order the blocks run in, record, per-block counts and
+    # every entry of C are the oracle's
     g, h = lib
-    m = n = 4096
     k = 192
     A0, B0 = wl.wide_rows(n, k, m, seed=13, row_lo=1000, row_hi=1040, spread=20)
     A, B = np.ascontiguousarray(B0.T), np.ascontiguousarray(A0.T)          # hard columns of C instead of hard rows
@@ -634,17 +635,24 @@ def test_per_tile_counts_with_the_tiles_dealt_by_slice_count(lib):
                                 v.pair_tiles)
     assert v.slices_min < v.slices_used
     np.testing.assert_array_equal(gm.tile_slice_counts(), tr.S_tile)
+    nti, ntj = tr.S_tile.shape
     heavy = np.argwhere(tr.S_tile == v.slices_used)
-    assert set(heavy[:, 1].tolist()) == {3, 4} and len(heavy) == 32         # two block columns of sixteen blocks
+    assert set(heavy[:, 1].tolist()) == {3, 4} and len(heavy) == 2 * nti       # two block columns
     np.testing.assert_array_equal(got, tr.C)
-    # the order table is a permutation of the blocks, and the 32 heavy blocks are the first round of the first XCD
-    # (positions 0..31 of the 256: the sorted sequence is dealt in groups of 32, group g to XCD g % 8)
+    # the order table is a permutation of the blocks, and the first round of the first XCD (positions 0..31: the
+    # sorted sequence is dealt in groups of 32, group g to XCD g % 8) holds heavy blocks only
     order = gm.tile_order()
-    assert sorted(order.tolist()) == list(range(256))
-    first_round = order[:32]
-    # block order of the GEMM: panels of 8 block columns, inside a panel row by row
-    tj_of = lambda lin: (lin // (8 * 16)) * 8 + (lin % (8 * 16)) % 8
-    assert {tj_of(int(v)) for v in first_round} == {3, 4}
+    assert sorted(order.tolist()) == list(range(nti * ntj))
+
+    def block_column(lin):      # block order of the GEMM: panels of 8 block columns, inside a panel row by row
+        panel = lin // (8 * nti)
+        width = min(8, ntj - panel * 8)
+        return panel * 8 + (lin - panel * 8 * nti) % width
+    assert {block_column(int(t)) for t in order[:32]} <= {3, 4}
+    # the blocks left to the k-split launch (behind the full round) are among the lightest
+    if nti * ntj > 256:
+        S_of = lambda lin: tr.S_tile[(lin - (lin // (8 * nti)) * 8 * nti) // min(8, ntj - (lin // (8 * nti)) * 8), block_column(lin)]
+        assert all(S_of(int(t)) == v.slices_min for t in order[256:])
 
 
 def test_per_tile_cost_model_keeps_a_localised_hard_region_emulated(lib):
