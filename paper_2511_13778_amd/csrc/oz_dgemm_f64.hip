@@ -8,10 +8,16 @@
 // v_mfma_f64_16x16x4_f64; 128x128 tile per workgroup, 4 waves of 64x64 (4x4 MFMA tiles),
 // K step 16 through double-buffered LDS.  op(B) feeds the row operand and op(A) the column
 // operand so that the result's lane index runs along i and stores to column-major C coalesce.
-// LDS banks: a tile row (one k) is 130 doubles = 260 dwords, i.e. 4 banks further per k.  Stores of a
-// k-contiguous operand (16 lanes on 16 different k, same row index) then hit 16 different bank
-// groups, and the MFMA operand reads pair lane groups whose k differ by 8 (= 32 banks): MFMA
-// number kk of a K step multiplies k = {kk, kk+8, kk+4, kk+12}, the same set for both operands.
+// LDS banks: a tile row (one k) is 130 doubles = 260 dwords, i.e. 4 banks further per k.  The MFMA
+// operand reads pair lane groups whose k differ by 8 (= 32 banks): MFMA number kk of a K step
+// multiplies k = {kk, kk+8, kk+4, kk+12}, the same set for both operands; they are conflict-free.
+// Stores of a k-contiguous operand (16 lanes on 16 different k, same row index) keep a two-way conflict
+// on the 32-bank store path (the counters show exactly 4 extra cycles per store); other row lengths
+// (129, 131, 133) give the same run time, so it is left as it is.
+// Tile loads go through a buffer descriptor (no vector address arithmetic in the K loop); ragged sizes
+// run the same loop with clamped rows and a short first K step; products with few tiles, or with a number
+// of tiles that is not a whole number of rounds, may split k over several workgroups per tile when the
+// caller provides scratch memory (partial tiles added in a fixed order by dgemm_f64_reduce_kernel).
 // The kernel is launched on every call and returns at once unless the verdict selected it.
 #include "oz_internal.h"
 
